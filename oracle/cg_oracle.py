@@ -1,0 +1,207 @@
+"""ctypes front end of the CPU oracle (``cg_ref.c``).
+
+TEST INFRASTRUCTURE ONLY: the tests, the smoke check and the CPU-baseline leg
+of the benchmark may import this module; the GPU library never does, and this
+module imports nothing from the GPU package.
+
+The arithmetic lives in ``cg_ref.c``; this file only widens inputs to the types
+the C code takes (double for the float path, int8 for the integer path),
+allocates outputs and fills the problem struct.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+import subprocess
+from pathlib import Path
+
+import numpy as np
+
+_HERE = Path(__file__).resolve().parent
+_SRC = _HERE / "cg_ref.c"
+_LIB = _HERE / "libcg_ref.so"
+
+RELU, AFFINE, RESIDUAL = 1, 2, 4
+
+
+def build(force: bool = False) -> Path:
+    """Compile cg_ref.c with gcc (plain -O2, OpenMP over output rows)."""
+    if force or not _LIB.exists() or _LIB.stat().st_mtime < _SRC.stat().st_mtime:
+        tmp = _LIB.with_suffix(".so.tmp%d" % os.getpid())
+        subprocess.check_call(
+            ["gcc", "-O2", "-fopenmp", "-fPIC", "-shared", "-std=c11", "-Wall", "-Wextra",
+             "-o", str(tmp), str(_SRC), "-lm"])
+        os.replace(tmp, _LIB)
+    return _LIB
+
+
+_pd = C.POINTER(C.c_double)
+_pi8 = C.POINTER(C.c_int8)
+_pi32 = C.POINTER(C.c_int32)
+_pu8 = C.POINTER(C.c_uint8)
+_pu32 = C.POINTER(C.c_uint32)
+_pu64 = C.POINTER(C.c_uint64)
+
+
+class _Problem(C.Structure):
+    _fields_ = [
+        ("n", C.c_int32), ("h", C.c_int32), ("w", C.c_int32), ("c_in", C.c_int32),
+        ("c_out", C.c_int32), ("c_base", C.c_int32),
+        ("kh", C.c_int32), ("kw", C.c_int32), ("stride", C.c_int32), ("pad", C.c_int32),
+        ("is_int", C.c_int32), ("out_i8", C.c_int32), ("epilogue", C.c_uint32),
+        ("two_sided", C.c_int32),
+        ("x", _pd), ("w_base", _pd), ("w_cond", _pd),
+        ("gate_mean", _pd), ("gate_var", _pd), ("delta", _pd), ("delta_hi", _pd),
+        ("gate_eps", C.c_double),
+        ("scale0", _pd), ("shift0", _pd), ("scale1", _pd), ("shift1", _pd),
+        ("residual", _pd),
+        ("xi", _pi8), ("wi_base", _pi8), ("wi_cond", _pi8),
+        ("thr", _pi32), ("rq_mult0", _pi32), ("rq_mult1", _pi32), ("rq_bias", _pi32),
+        ("rq_shift", C.c_int32), ("residual_i8", _pi8), ("rq_res_mult", C.c_int32),
+        ("P", _pd), ("R", _pd), ("y", _pd), ("y_other", _pd), ("margin", _pd),
+        ("Pi", _pi32), ("Ri", _pi32), ("yi", _pi32), ("yi_other", _pi32),
+        ("d", _pu8), ("bitmap", _pu32), ("counts", _pu32), ("macs", _pu64),
+    ]
+
+
+_lib = None
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build()
+        _lib = C.CDLL(str(_LIB))
+        _lib.cg_ref_forward.argtypes = [C.POINTER(_Problem)]
+        _lib.cg_ref_forward.restype = C.c_int
+    return _lib
+
+
+def out_hw(h, w, kh, kw, stride, pad):
+    ho = (h + 2 * pad - kh) // stride + 1 if h + 2 * pad - kh >= 0 else 0
+    wo = (w + 2 * pad - kw) // stride + 1 if w + 2 * pad - kw >= 0 else 0
+    return ho, wo
+
+
+def _as(a, dtype):
+    return None if a is None else np.ascontiguousarray(np.asarray(a), dtype=dtype)
+
+
+def _ptr(a, ptype):
+    return None if a is None else a.ctypes.data_as(ptype)
+
+
+def forward_float(x, w_base, w_cond, *, stride=1, pad=1, gate_mean=None, gate_var=None, delta=None,
+                  delta_hi=None, gate_eps=0.0, scale0=None, shift0=None, scale1=None, shift1=None,
+                  residual=None, epilogue=RELU, want_partials=True):
+    """Float path.  x [N,H,W,C_in]; w_base [C_out,kh,kw,C_base]; w_cond [C_out,kh,kw,C_in-C_base]
+    (None or zero-width for a dense layer).  Every array is widened to float64 exactly."""
+    lib = _load()
+    x = _as(x, np.float64)
+    w_base = _as(w_base, np.float64)
+    n, h, w, c_in = x.shape
+    c_out, kh, kw, c_base = w_base.shape
+    c_r = c_in - c_base
+    if c_r > 0:
+        w_cond = _as(w_cond, np.float64)
+        assert w_cond.shape == (c_out, kh, kw, c_r), w_cond.shape
+    else:
+        w_cond = None
+    ho, wo = out_hw(h, w, kh, kw, stride, pad)
+    shape = (n, ho, wo, c_out)
+    words = (c_out + 31) // 32
+    keep = dict(x=x, w_base=w_base, w_cond=w_cond)
+    for name, v in (("gate_mean", gate_mean), ("gate_var", gate_var), ("delta", delta), ("delta_hi", delta_hi),
+                    ("scale0", scale0), ("shift0", shift0), ("scale1", scale1), ("shift1", shift1)):
+        v = _as(v, np.float64)
+        if v is not None:
+            if v.ndim == 0:
+                v = np.full(c_out, float(v))
+            assert v.shape == (c_out,), (name, v.shape)
+        keep[name] = v
+    residual = _as(residual, np.float64)
+    if residual is not None:
+        assert residual.shape == shape
+    out = dict(
+        y=np.empty(shape), y_other=np.empty(shape), margin=np.empty(shape),
+        d=np.empty(shape, np.uint8), bitmap=np.empty((n * ho * wo, words), np.uint32),
+        counts=np.empty(2 + n * c_out, np.uint32))
+    if want_partials:
+        out["P"] = np.empty(shape)
+        out["R"] = np.empty(shape)
+    macs = C.c_uint64(0)
+    p = _Problem()
+    p.n, p.h, p.w, p.c_in, p.c_out, p.c_base = n, h, w, c_in, c_out, c_base
+    p.kh, p.kw, p.stride, p.pad = kh, kw, stride, pad
+    p.is_int, p.out_i8, p.epilogue = 0, 0, epilogue
+    p.two_sided = 1 if delta_hi is not None else 0
+    p.gate_eps = gate_eps
+    for name in ("x", "w_base", "w_cond", "gate_mean", "gate_var", "delta", "delta_hi",
+                 "scale0", "shift0", "scale1", "shift1"):
+        setattr(p, name, _ptr(keep[name], _pd))
+    p.residual = _ptr(residual, _pd)
+    for name in ("y", "y_other", "margin", "P", "R"):
+        if name in out:
+            setattr(p, name, _ptr(out[name], _pd))
+    p.d = _ptr(out["d"], _pu8)
+    p.bitmap = _ptr(out["bitmap"], _pu32)
+    p.counts = _ptr(out["counts"], _pu32)
+    p.macs = C.pointer(macs)
+    rc = lib.cg_ref_forward(C.byref(p))
+    if rc != 0:
+        raise ValueError("cg_ref_forward rejected the problem (rc=%d)" % rc)
+    out["macs"] = int(macs.value)
+    out["fired"] = int(out["counts"][0]) | (int(out["counts"][1]) << 32)
+    return out
+
+
+def forward_int8(x, w_base, w_cond, thr, *, stride=1, pad=1, out_i8=False, rq_mult0=None, rq_mult1=None,
+                 rq_bias=None, rq_shift=0, residual=None, rq_res_mult=0, epilogue=RELU, want_partials=True):
+    """Integer path: int8 inputs, int32 accumulation, int32 thresholds; exact."""
+    lib = _load()
+    x = _as(x, np.int8)
+    w_base = _as(w_base, np.int8)
+    n, h, w, c_in = x.shape
+    c_out, kh, kw, c_base = w_base.shape
+    c_r = c_in - c_base
+    w_cond = _as(w_cond, np.int8) if c_r > 0 else None
+    if w_cond is not None:
+        assert w_cond.shape == (c_out, kh, kw, c_r)
+    ho, wo = out_hw(h, w, kh, kw, stride, pad)
+    shape = (n, ho, wo, c_out)
+    words = (c_out + 31) // 32
+    thr = _as(thr, np.int32)
+    rq_mult0, rq_mult1, rq_bias = _as(rq_mult0, np.int32), _as(rq_mult1, np.int32), _as(rq_bias, np.int32)
+    residual = _as(residual, np.int8)
+    out = dict(
+        y=np.empty(shape, np.int32), y_other=np.empty(shape, np.int32), margin=np.empty(shape),
+        d=np.empty(shape, np.uint8), bitmap=np.empty((n * ho * wo, words), np.uint32),
+        counts=np.empty(2 + n * c_out, np.uint32))
+    if want_partials:
+        out["P"] = np.empty(shape, np.int32)
+        out["R"] = np.empty(shape, np.int32)
+    macs = C.c_uint64(0)
+    p = _Problem()
+    p.n, p.h, p.w, p.c_in, p.c_out, p.c_base = n, h, w, c_in, c_out, c_base
+    p.kh, p.kw, p.stride, p.pad = kh, kw, stride, pad
+    p.is_int, p.out_i8, p.epilogue = 1, int(bool(out_i8)), epilogue
+    p.xi, p.wi_base, p.wi_cond = _ptr(x, _pi8), _ptr(w_base, _pi8), _ptr(w_cond, _pi8)
+    p.thr = _ptr(thr, _pi32)
+    p.rq_mult0, p.rq_mult1, p.rq_bias = _ptr(rq_mult0, _pi32), _ptr(rq_mult1, _pi32), _ptr(rq_bias, _pi32)
+    p.rq_shift = rq_shift
+    p.residual_i8 = _ptr(residual, _pi8)
+    p.rq_res_mult = rq_res_mult
+    p.yi, p.yi_other = _ptr(out["y"], _pi32), _ptr(out["y_other"], _pi32)
+    p.margin = _ptr(out["margin"], _pd)
+    if want_partials:
+        p.Pi, p.Ri = _ptr(out["P"], _pi32), _ptr(out["R"], _pi32)
+    p.d = _ptr(out["d"], _pu8)
+    p.bitmap = _ptr(out["bitmap"], _pu32)
+    p.counts = _ptr(out["counts"], _pu32)
+    p.macs = C.pointer(macs)
+    rc = lib.cg_ref_forward(C.byref(p))
+    if rc != 0:
+        raise ValueError("cg_ref_forward rejected the problem (rc=%d)" % rc)
+    out["macs"] = int(macs.value)
+    out["fired"] = int(out["counts"][0]) | (int(out["counts"][1]) << 32)
+    return out

@@ -1,0 +1,257 @@
+/*
+ * CPU oracle for the channel-gated convolution layer.
+ *
+ * TEST INFRASTRUCTURE ONLY.  This file is the slow, plain definition of the
+ * layer that the GPU library is checked against.  It shares no code with the
+ * GPU path and must never be called from it.  Only the tests, the smoke check
+ * and the CPU-baseline leg of the benchmark may load it.
+ *
+ * What it computes (paper: "Channel Gating Neural Networks", Sec. 3.1-3.2):
+ *
+ *   split     x = [x_p, x_r] along channels, x_p = the first c_base channels,
+ *             W = [W_p, W_r] likewise, so W*x = W_p*x_p + W_r*x_r   (Sec. 3.1)
+ *   base      P = W_p * x_p        (always evaluated)               (Sec. 3.1)
+ *   gate      d = theta(P - Delta*sqrt(Var) - E), theta(v)=1 iff v>=0
+ *                                                   (Heaviside step, merged
+ *                                                    BN gate of Sec. 3.2)
+ *   cond.     R = W_r * x_r        (needed only where d = 1)        (Sec. 3.1)
+ *   output    y = f(P) where d = 0, f(P + R) where d = 1            (Eq. 1)
+ *
+ * "*" is the usual deep-learning cross-correlation with symmetric zero
+ * padding and floor output size; the paper does not say, this is the reading
+ * taken.  f is an optional per-channel scale/shift (inference-time batch norm,
+ * Sec. 3.1 footnote; one pair per branch because training uses two BNs,
+ * Sec. 4), an optional residual add and an optional ReLU.
+ *
+ * Precision: the float path takes every input already widened to double and
+ * accumulates in double.  The integer path takes int8 inputs, accumulates in
+ * int32 and compares with an int32 threshold, so it is exact.
+ *
+ * The loops below are the definition written out: n, ho, wo, co, r, s, c.
+ * OpenMP only spreads (n, ho) rows over threads; no blocking or reordering.
+ *
+ * All tensors are NHWC: x[n][h][w][c_in], outputs [n][ho][wo][c_out].
+ * Weights: w_base[c_out][kh][kw][c_base], w_cond[c_out][kh][kw][c_in-c_base].
+ */
+#include <math.h>
+#include <stddef.h>
+#include <stdint.h>
+#include <string.h>
+
+#define CG_REF_RELU 1u
+#define CG_REF_AFFINE 2u
+#define CG_REF_RESIDUAL 4u
+
+typedef struct cg_ref_problem {
+  int32_t n, h, w, c_in, c_out, c_base;
+  int32_t kh, kw, stride, pad;
+  int32_t is_int;      /* 0: float path (double inputs), 1: int8 path */
+  int32_t out_i8;      /* int path: 1 = requantise to int8, 0 = raw int32 sum */
+  uint32_t epilogue;   /* CG_REF_* flags */
+  int32_t two_sided;   /* float path: also require z <= delta_hi (Sec. 3.2,
+                          gate for saturating activations) */
+
+  /* float path inputs */
+  const double *x, *w_base, *w_cond;
+  const double *gate_mean, *gate_var, *delta, *delta_hi; /* [c_out] */
+  double gate_eps;
+  const double *scale0, *shift0, *scale1, *shift1;       /* [c_out] or NULL */
+  const double *residual;                                /* like y, or NULL */
+
+  /* int path inputs */
+  const int8_t *xi, *wi_base, *wi_cond;
+  const int32_t *thr;                                    /* [c_out] */
+  const int32_t *rq_mult0, *rq_mult1, *rq_bias;          /* [c_out] */
+  int32_t rq_shift;
+  const int8_t *residual_i8;
+  int32_t rq_res_mult;
+
+  /* outputs; any may be NULL */
+  double *P, *R;          /* float path partial sums */
+  double *y, *y_other;    /* y under the oracle's decision / under the opposite one */
+  double *margin;         /* |z - Delta| in normalised units */
+  int32_t *Pi, *Ri;       /* int path partial sums */
+  int32_t *yi, *yi_other;
+  uint8_t *d;             /* one byte per activation */
+  uint32_t *bitmap;       /* [M][ceil(c_out/32)], bit (co&31) of word co>>5 */
+  uint32_t *counts;       /* [2 + n*c_out]: total (lo,hi), then per (image, channel) */
+  uint64_t *macs;         /* multiply-adds on in-range taps: base everywhere,
+                             conditional only where the gate fired (Eq. 1) */
+} cg_ref_problem;
+
+static int out_size(int in, int k, int stride, int pad) {
+  int span = in + 2 * pad - k;
+  if (span < 0) return 0;
+  return span / stride + 1;
+}
+
+int cg_ref_out_h(const cg_ref_problem *p) { return out_size(p->h, p->kh, p->stride, p->pad); }
+int cg_ref_out_w(const cg_ref_problem *p) { return out_size(p->w, p->kw, p->stride, p->pad); }
+
+/* f for the float path: branch-specific affine, residual, ReLU (Eq. 1's f). */
+static double finish_float(const cg_ref_problem *p, double s, int fired, int co, size_t o) {
+  double a = s;
+  if (p->epilogue & CG_REF_AFFINE) {
+    const double *sc = fired ? p->scale1 : p->scale0;
+    const double *sh = fired ? p->shift1 : p->shift0;
+    a = (sc ? sc[co] : 1.0) * s + (sh ? sh[co] : 0.0);
+  }
+  if ((p->epilogue & CG_REF_RESIDUAL) && p->residual) a += p->residual[o];
+  if ((p->epilogue & CG_REF_RELU) && a < 0.0) a = 0.0;
+  return a;
+}
+
+/* f for the int path.  Without requantisation the int32 sum is the output
+ * (residual add and ReLU still apply).  With it: fixed-point multiply, bias,
+ * residual, round-half-up shift, clamp. */
+static int32_t finish_int(const cg_ref_problem *p, int32_t s, int fired, int co, size_t o) {
+  if (!p->out_i8) {
+    int64_t a = s;
+    if ((p->epilogue & CG_REF_RESIDUAL) && p->residual_i8)
+      a += (int64_t)p->residual_i8[o] * p->rq_res_mult;
+    if ((p->epilogue & CG_REF_RELU) && a < 0) a = 0;
+    if (a > INT32_MAX) a = INT32_MAX;
+    if (a < INT32_MIN) a = INT32_MIN;
+    return (int32_t)a;
+  }
+  const int32_t *mu = fired ? p->rq_mult1 : p->rq_mult0;
+  int64_t t = (int64_t)s * (mu ? mu[co] : 1);
+  if (p->rq_bias) t += (int64_t)p->rq_bias[co] * ((int64_t)1 << p->rq_shift);
+  if ((p->epilogue & CG_REF_RESIDUAL) && p->residual_i8)
+    t += (int64_t)p->residual_i8[o] * p->rq_res_mult;
+  if (p->rq_shift > 0) {
+    t += (int64_t)1 << (p->rq_shift - 1);
+    /* arithmetic shift = floor division by 2^shift */
+    int64_t q = t / ((int64_t)1 << p->rq_shift);
+    if (t % ((int64_t)1 << p->rq_shift) < 0) q -= 1;
+    t = q;
+  }
+  int64_t lo = (p->epilogue & CG_REF_RELU) ? 0 : -128;
+  if (t < lo) t = lo;
+  if (t > 127) t = 127;
+  return (int32_t)t;
+}
+
+/*
+ * Returns 0 on success, 1 on an invalid problem.  counts and bitmap are
+ * overwritten in full.
+ */
+int cg_ref_forward(const cg_ref_problem *p) {
+  if (!p || p->n < 0 || p->h <= 0 || p->w <= 0 || p->c_in <= 0 || p->c_out <= 0) return 1;
+  if (p->c_base <= 0 || p->c_base > p->c_in) return 1;
+  if (p->kh <= 0 || p->kw <= 0 || p->stride <= 0 || p->pad < 0) return 1;
+  if (p->is_int ? (!p->xi || !p->wi_base) : (!p->x || !p->w_base)) return 1;
+
+  const int N = p->n, H = p->h, W = p->w, C = p->c_in, CO = p->c_out, CP = p->c_base;
+  const int CR = C - CP;
+  if (CR > 0 && (p->is_int ? !p->wi_cond : !p->w_cond)) return 1;
+  const int gated = CR > 0;
+  if (gated && (p->is_int ? !p->thr : (!p->gate_mean || !p->gate_var || !p->delta))) return 1;
+  const int KH = p->kh, KW = p->kw, ST = p->stride, PD = p->pad;
+  const int HO = cg_ref_out_h(p), WO = cg_ref_out_w(p);
+  const int words = (CO + 31) / 32;
+  const size_t M = (size_t)N * HO * WO;
+
+  if (p->bitmap) memset(p->bitmap, 0, M * words * sizeof(uint32_t));
+  if (p->counts) memset(p->counts, 0, (2 + (size_t)N * CO) * sizeof(uint32_t));
+
+  uint64_t total_fired = 0, total_macs = 0;
+
+#pragma omp parallel for collapse(2) schedule(static) reduction(+ : total_fired, total_macs)
+  for (int n = 0; n < N; ++n) {
+    for (int ho = 0; ho < HO; ++ho) {
+      for (int wo = 0; wo < WO; ++wo) {
+        const size_t m = ((size_t)n * HO + ho) * WO + wo;
+        for (int co = 0; co < CO; ++co) {
+          const size_t o = m * CO + co;
+          double accP = 0.0, accR = 0.0;
+          int32_t iP = 0, iR = 0;
+          uint64_t taps_in = 0;
+          for (int r = 0; r < KH; ++r) {
+            const int hi = ho * ST - PD + r;
+            if (hi < 0 || hi >= H) continue;
+            for (int s = 0; s < KW; ++s) {
+              const int wi = wo * ST - PD + s;
+              if (wi < 0 || wi >= W) continue;
+              ++taps_in;
+              const size_t xo = (((size_t)n * H + hi) * W + wi) * C;
+              const size_t wbo = (((size_t)co * KH + r) * KW + s) * CP;
+              const size_t wco = (((size_t)co * KH + r) * KW + s) * CR;
+              if (p->is_int) {
+                for (int c = 0; c < CP; ++c) iP += (int32_t)p->xi[xo + c] * (int32_t)p->wi_base[wbo + c];
+                for (int c = 0; c < CR; ++c) iR += (int32_t)p->xi[xo + CP + c] * (int32_t)p->wi_cond[wco + c];
+              } else {
+                for (int c = 0; c < CP; ++c) accP += p->x[xo + c] * p->w_base[wbo + c];
+                for (int c = 0; c < CR; ++c) accR += p->x[xo + CP + c] * p->w_cond[wco + c];
+              }
+            }
+          }
+
+          /* gate: Heaviside step on the normalised partial sum, ties fire */
+          int fired = 0;
+          double marg = INFINITY;
+          if (gated) {
+            if (p->is_int) {
+              fired = iP >= p->thr[co];
+              marg = fabs((double)iP - (double)p->thr[co]);
+            } else {
+              const double sd = sqrt(p->gate_var[co] + p->gate_eps);
+              const double dl = p->delta[co];
+              if (isinf(dl)) {
+                fired = dl < 0;
+              } else {
+                const double t = p->gate_mean[co] + dl * sd;
+                fired = accP >= t;
+                marg = sd > 0 ? fabs((accP - p->gate_mean[co]) / sd - dl) : fabs(accP - t);
+              }
+              if (p->two_sided && p->delta_hi && !isinf(p->delta_hi[co])) {
+                const double th = p->gate_mean[co] + p->delta_hi[co] * sd;
+                fired = fired && (accP <= th);
+                const double mh = sd > 0 ? fabs((accP - p->gate_mean[co]) / sd - p->delta_hi[co]) : fabs(accP - th);
+                if (mh < marg) marg = mh;
+              } else if (p->two_sided && p->delta_hi && p->delta_hi[co] < 0) {
+                fired = 0; /* upper threshold -inf: nothing passes */
+              }
+            }
+          } else {
+            fired = 1; /* no conditional channels: plain dense convolution */
+          }
+
+          total_macs += taps_in * (uint64_t)(CP + (fired ? CR : 0));
+
+          if (p->is_int) {
+            const int32_t s_dec = fired ? iP + iR : iP;
+            const int32_t s_oth = fired ? iP : iP + iR;
+            if (p->Pi) p->Pi[o] = iP;
+            if (p->Ri) p->Ri[o] = iR;
+            if (p->yi) p->yi[o] = finish_int(p, s_dec, fired, co, o);
+            if (p->yi_other) p->yi_other[o] = finish_int(p, s_oth, !fired, co, o);
+          } else {
+            const double s_dec = fired ? accP + accR : accP;
+            const double s_oth = fired ? accP : accP + accR;
+            if (p->P) p->P[o] = accP;
+            if (p->R) p->R[o] = accR;
+            if (p->y) p->y[o] = finish_float(p, s_dec, fired, co, o);
+            if (p->y_other) p->y_other[o] = finish_float(p, s_oth, !fired, co, o);
+          }
+          if (p->margin) p->margin[o] = marg;
+          if (p->d) p->d[o] = (uint8_t)(gated ? fired : 0);
+          if (gated && fired) {
+            ++total_fired;
+            if (p->bitmap) p->bitmap[m * words + (co >> 5)] |= 1u << (co & 31);
+            if (p->counts) {
+#pragma omp atomic
+              p->counts[2 + (size_t)n * CO + co] += 1u;
+            }
+          }
+        }
+      }
+    }
+  }
+  if (p->counts) {
+    p->counts[0] = (uint32_t)(total_fired & 0xffffffffu);
+    p->counts[1] = (uint32_t)(total_fired >> 32);
+  }
+  if (p->macs) *p->macs = total_macs;
+  return 0;
+}

@@ -1,0 +1,363 @@
+"""Pins for the CPU oracle: everything here checks ``oracle/`` against something
+other than itself -- brute force in exact arithmetic, a library convolution,
+closed forms, hand-built gate maps and a hand-computed fixture.  No GPU."""
+from fractions import Fraction
+from pathlib import Path
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import cg_oracle as O
+from tests.brute import gated_conv_brute
+
+GOLDEN = Path(__file__).parent / "golden"
+
+
+def lib_conv(x, w, stride, pad):
+    """torch CPU fp64 convolution on NHWC / [CO,KH,KW,C] arrays."""
+    xt = torch.from_numpy(np.asarray(x, np.float64)).permute(0, 3, 1, 2)
+    wt = torch.from_numpy(np.asarray(w, np.float64)).permute(0, 3, 1, 2)
+    return torch.nn.functional.conv2d(xt, wt, stride=stride, padding=pad).permute(0, 2, 3, 1).numpy()
+
+
+def rand_problem(rng, n, h, w, c_in, c_out, g, k=3, ints=False):
+    c_base = c_in // g
+    if ints:
+        x = rng.integers(0, 6, (n, h, w, c_in)).astype(np.float64)
+        wt = rng.integers(-3, 4, (c_out, k, k, c_in)).astype(np.float64)
+    else:
+        x = np.maximum(rng.standard_normal((n, h, w, c_in)), 0)
+        wt = rng.standard_normal((c_out, k, k, c_in)) * 0.3
+    return x, np.ascontiguousarray(wt[..., :c_base]), np.ascontiguousarray(wt[..., c_base:])
+
+
+# ---------------------------------------------------------------------------
+# P1: brute force in exact rational arithmetic on tiny shapes
+# ---------------------------------------------------------------------------
+@pytest.mark.parametrize("stride,pad", [(1, 1), (2, 1), (1, 0), (2, 0)])
+@pytest.mark.parametrize("g", [1, 2, 4, 8])
+def test_brute_force_float(stride, pad, g):
+    rng = np.random.default_rng(100 * stride + 10 * pad + g)
+    n, h, w, c_in, c_out = 2, 6, 5, 8, 4
+    x, wb, wc = rand_problem(rng, n, h, w, c_in, c_out, g)
+    mean = rng.standard_normal(c_out) * 0.1
+    var = rng.uniform(0.5, 2.0, c_out)
+    delta = rng.standard_normal(c_out) * 0.5
+    out = O.forward_float(x, wb, wc, stride=stride, pad=pad, gate_mean=mean, gate_var=var, delta=delta,
+                          epilogue=0)
+    thr = [Fraction(float(mean[c] + delta[c] * np.sqrt(var[c]))) for c in range(c_out)]
+    P, R, D, S = gated_conv_brute(x.tolist(), wb.tolist(), wc.tolist() if g > 1 else None, stride, pad, thr)
+    P = np.array(P, dtype=np.float64)
+    R = np.array(R, dtype=np.float64)
+    S = np.array(S, dtype=np.float64)
+    D = np.array(D, dtype=np.uint8)
+    assert out["P"].shape == P.shape
+    np.testing.assert_allclose(out["P"], P, rtol=0, atol=1e-12)
+    np.testing.assert_allclose(out["R"], R, rtol=0, atol=1e-12)
+    # decisions: equal except where the exact sum sits within rounding of the threshold
+    thr_f = np.array([float(t) for t in thr])
+    safe = np.abs(P - thr_f) > 1e-9
+    assert np.array_equal(out["d"][safe], D[safe])
+    assert safe.mean() > 0.99
+    agree = out["d"] == D
+    np.testing.assert_allclose(out["y"][agree], S[agree], rtol=0, atol=1e-12)
+
+
+@pytest.mark.parametrize("stride,pad", [(1, 1), (2, 1), (1, 0)])
+@pytest.mark.parametrize("g", [1, 2, 4])
+def test_brute_force_int8_exact(stride, pad, g):
+    rng = np.random.default_rng(7 + 100 * stride + 10 * pad + g)
+    n, h, w, c_in, c_out = 2, 5, 6, 8, 4
+    x = rng.integers(0, 128, (n, h, w, c_in)).astype(np.int8)
+    wt = rng.integers(-127, 128, (c_out, 3, 3, c_in)).astype(np.int8)
+    cb = c_in // g
+    wb, wc = np.ascontiguousarray(wt[..., :cb]), np.ascontiguousarray(wt[..., cb:])
+    thr = rng.integers(-3000, 3000, c_out).astype(np.int32)
+    out = O.forward_int8(x, wb, wc, thr, stride=stride, pad=pad, epilogue=0)
+    P, R, D, S = gated_conv_brute(x.tolist(), wb.tolist(), wc.tolist() if g > 1 else None, stride, pad,
+                                  thr.tolist(), exact=False)
+    assert np.array_equal(out["P"], np.array(P, dtype=np.int64))
+    assert np.array_equal(out["R"], np.array(R, dtype=np.int64))
+    assert np.array_equal(out["d"], np.array(D, dtype=np.uint8))
+    assert np.array_equal(out["y"], np.array(S, dtype=np.int64))
+
+
+# ---------------------------------------------------------------------------
+# P2 / P3: Delta = -inf is the dense convolution, Delta = +inf the base path alone
+# (the split identity W*x = W_p*x_p + W_r*x_r and the d = 0 branch of Eq. 1)
+# ---------------------------------------------------------------------------
+@pytest.mark.parametrize("stride,pad,h,w", [(1, 1, 9, 7), (2, 1, 9, 7), (2, 1, 8, 8), (1, 0, 6, 10), (2, 0, 7, 5)])
+@pytest.mark.parametrize("k", [3, 1])
+def test_delta_infinite_matches_library_conv(stride, pad, h, w, k):
+    rng = np.random.default_rng(stride * 1000 + h * 10 + w + k)
+    n, c_in, c_out, g = 3, 12, 40, 4
+    x, wb, wc = rand_problem(rng, n, h, w, c_in, c_out, g, k=k)
+    pad = pad if k == 3 else 0
+    mean, var = rng.standard_normal(c_out), rng.uniform(0.1, 2, c_out)
+    full = lib_conv(x, np.concatenate([wb, wc], axis=-1), stride, pad)
+    base = lib_conv(x[..., : c_in // g], wb, stride, pad)
+    lo = O.forward_float(x, wb, wc, stride=stride, pad=pad, gate_mean=mean, gate_var=var,
+                         delta=np.full(c_out, -np.inf), epilogue=0)
+    hi = O.forward_float(x, wb, wc, stride=stride, pad=pad, gate_mean=mean, gate_var=var,
+                         delta=np.full(c_out, np.inf), epilogue=0)
+    assert lo["y"].shape == full.shape
+    np.testing.assert_allclose(lo["y"], full, rtol=1e-12, atol=1e-12)
+    np.testing.assert_allclose(hi["y"], base, rtol=1e-12, atol=1e-12)
+    m = full.shape[0] * full.shape[1] * full.shape[2]
+    assert lo["d"].all() and not hi["d"].any()
+    assert lo["fired"] == m * c_out and hi["fired"] == 0
+    # bitmap: c_out = 40 -> two words per pixel, upper 24 bits of the second word unused and zero
+    assert lo["bitmap"].shape == (m, 2)
+    assert (lo["bitmap"][:, 0] == 0xFFFFFFFF).all() and (lo["bitmap"][:, 1] == 0xFF).all()
+    assert not hi["bitmap"].any()
+    assert (lo["counts"][2:] == full.shape[1] * full.shape[2]).all()
+    # executed multiply-adds: every in-range tap of every channel (dense), base channels only (never fires)
+    ones = lib_conv(np.ones((1, h, w, 1)), np.ones((1, k, k, 1)), stride, pad)  # in-range taps per output
+    taps = int(round(ones.sum())) * n
+    assert lo["macs"] == taps * c_out * c_in
+    assert hi["macs"] == taps * c_out * (c_in // g)
+
+
+def test_dense_layer_has_no_gate():
+    rng = np.random.default_rng(5)
+    x, wb, _ = rand_problem(rng, 2, 5, 5, 8, 6, 1)
+    out = O.forward_float(x, wb, None, stride=1, pad=1, epilogue=O.RELU)
+    np.testing.assert_allclose(out["y"], np.maximum(lib_conv(x, wb, 1, 1), 0), rtol=1e-12, atol=1e-12)
+    assert out["fired"] == 0 and not out["bitmap"].any() and not out["d"].any()
+
+
+# ---------------------------------------------------------------------------
+# gate formula and executed-work identity on integer-valued data (exact in fp64)
+# ---------------------------------------------------------------------------
+def test_gate_rule_matches_normalised_form_and_mac_identity():
+    rng = np.random.default_rng(11)
+    n, h, w, c_in, c_out, g = 2, 8, 8, 8, 8, 4
+    x, wb, wc = rand_problem(rng, n, h, w, c_in, c_out, g, ints=True)
+    P = lib_conv(x[..., :2], wb, 1, 1)
+    R = lib_conv(x[..., 2:], wc, 1, 1)
+    mean = np.round(P.reshape(-1, c_out).mean(0))
+    var = np.full(c_out, 4.0)           # sigma = 2 exactly
+    delta = np.array([0.5, -0.5, 1.0, 0.0, 2.0, -1.5, 0.25, 3.0])
+    out = O.forward_float(x, wb, wc, gate_mean=mean, gate_var=var, delta=delta, epilogue=0)
+    z = (P - mean) / 2.0
+    d = (z >= delta).astype(np.uint8)                       # normalise, then compare with Delta
+    assert np.array_equal(out["d"], d)
+    np.testing.assert_array_equal(out["margin"], np.abs(z - delta))
+    np.testing.assert_array_equal(out["y"], P + d * R)
+    np.testing.assert_array_equal(out["y_other"], P + (1 - d) * R)
+    assert out["fired"] == int(d.sum())
+    assert np.array_equal(out["counts"][2:].reshape(n, c_out), d.sum(axis=(1, 2)))
+    taps = lib_conv(np.ones((1, h, w, 1)), np.ones((1, 3, 3, 1)), 1, 1)[0, :, :, 0]
+    want = int((taps[None, :, :, None] * (2 + 6 * d)).sum())
+    assert out["macs"] == want
+    # interior-only formula: M*C_out*K_p + fired*K_r when no tap is cut by the border
+    out0 = O.forward_float(x, wb, wc, pad=0, gate_mean=mean, gate_var=var, delta=delta, epilogue=0)
+    m0 = n * 6 * 6
+    assert out0["macs"] == m0 * c_out * 9 * 2 + out0["fired"] * 9 * 6
+
+
+def test_tie_fires():
+    # integer data, threshold hit exactly: theta(0) = 1
+    x = np.ones((1, 3, 3, 2))
+    wb = np.ones((1, 3, 3, 1))
+    wc = np.ones((1, 3, 3, 1))
+    out = O.forward_float(x, wb, wc, gate_mean=[1.0], gate_var=[4.0], delta=[2.5], epilogue=0)  # t = 6
+    assert out["d"].reshape(3, 3).tolist() == [[0, 1, 0], [1, 1, 1], [0, 1, 0]]
+    assert out["margin"].reshape(3, 3)[0, 1] == 0.0
+    out = O.forward_float(x, wb, wc, gate_mean=[1.0], gate_var=[4.0], delta=[2.5 + 1e-9], epilogue=0)
+    assert out["d"].reshape(3, 3).tolist() == [[0, 0, 0], [0, 1, 0], [0, 0, 0]]
+    # eps enters under the square root: Var + eps = 4
+    out = O.forward_float(x, wb, wc, gate_mean=[1.0], gate_var=[3.0], gate_eps=1.0, delta=[2.5], epilogue=0)
+    assert out["d"].sum() == 5
+
+
+# ---------------------------------------------------------------------------
+# hand-computed fixture
+# ---------------------------------------------------------------------------
+def test_closed_form_fixture():
+    rows = {}
+    for line in (GOLDEN / "closed_form_3x3.txt").read_text().splitlines():
+        if line and not line.startswith("#"):
+            k, *v = line.split()
+            rows[k] = [int(t) for t in v]
+    x = np.ones((1, 3, 3, 2))
+    out = O.forward_float(x, np.ones((1, 3, 3, 1)), np.ones((1, 3, 3, 1)), gate_mean=[0.0], gate_var=[1.0],
+                          delta=[5.0], epilogue=O.RELU)
+    assert out["P"].reshape(-1).tolist() == rows["P"]
+    assert out["d"].reshape(-1).tolist() == rows["d"]
+    assert out["y"].reshape(-1).tolist() == rows["y"]
+    assert out["bitmap"].reshape(-1).tolist() == rows["bitmap"]
+    assert out["fired"] == rows["fired"][0]
+    assert out["counts"].tolist() == [5, 0, 5]
+    # same numbers through the int8 path, threshold 5
+    oi = O.forward_int8(x.astype(np.int8), np.ones((1, 3, 3, 1), np.int8), np.ones((1, 3, 3, 1), np.int8),
+                        np.array([5], np.int32), epilogue=O.RELU)
+    assert oi["y"].reshape(-1).tolist() == rows["y"] and oi["bitmap"].reshape(-1).tolist() == rows["bitmap"]
+
+
+# ---------------------------------------------------------------------------
+# P4: painted gate maps.  A one-hot base weight copies a shifted input channel into P,
+# so the decision map is a known picture; pins tap orientation, stride, pad, bit order.
+# ---------------------------------------------------------------------------
+@pytest.mark.parametrize("r,s", [(0, 0), (0, 2), (1, 1), (2, 0), (2, 1)])
+@pytest.mark.parametrize("stride", [1, 2])
+def test_one_hot_tap_paints_shifted_image(r, s, stride):
+    rng = np.random.default_rng(r * 3 + s)
+    n, h, w, c_in, c_out, cb = 2, 7, 9, 6, 35, 2
+    x = rng.integers(0, 10, (n, h, w, c_in)).astype(np.float64)
+    wb = np.zeros((c_out, 3, 3, cb))
+    src = rng.integers(0, cb, c_out)
+    wb[np.arange(c_out), r, s, src] = 1.0
+    wc = rng.integers(-2, 3, (c_out, 3, 3, c_in - cb)).astype(np.float64)
+    thr = rng.integers(1, 9, c_out).astype(np.float64)
+    out = O.forward_float(x, wb, wc, stride=stride, pad=1, gate_mean=np.zeros(c_out), gate_var=np.ones(c_out),
+                          delta=thr, epilogue=0)
+    ho, wo = out["y"].shape[1:3]
+    xp = np.zeros((n, h + 2, w + 2, c_in))
+    xp[:, 1:-1, 1:-1] = x
+    want_p = np.empty((n, ho, wo, c_out))
+    for a in range(ho):
+        for b in range(wo):
+            want_p[:, a, b, :] = xp[:, a * stride + r, b * stride + s, :][:, src]
+    np.testing.assert_array_equal(out["P"], want_p)
+    d = want_p >= thr
+    assert np.array_equal(out["d"], d.astype(np.uint8))
+    # bitmap layout: row m = (n*Ho + ho)*Wo + wo, word co>>5, bit co&31
+    flat = d.reshape(-1, c_out)
+    for m in (0, 1, wo, flat.shape[0] - 1):
+        for co in (0, 1, 31, 32, 34):
+            bit = (int(out["bitmap"][m, co >> 5]) >> (co & 31)) & 1
+            assert bit == int(flat[m, co])
+    assert (out["bitmap"][:, 1] >> 3 == 0).all()
+    assert sum(bin(int(v)).count("1") for v in out["bitmap"].reshape(-1)) == out["fired"] == int(d.sum())
+
+
+def test_zero_base_region_never_fires_with_positive_threshold():
+    rng = np.random.default_rng(3)
+    x = np.maximum(rng.standard_normal((1, 10, 10, 8)), 0)
+    x[:, :, :5, :2] = 0.0                      # base channels are zero on the left half
+    wb = rng.standard_normal((4, 3, 3, 2))
+    wc = rng.standard_normal((4, 3, 3, 6))
+    out = O.forward_float(x, wb, wc, gate_mean=np.zeros(4), gate_var=np.ones(4), delta=np.full(4, 0.01), epilogue=0)
+    assert not out["d"][:, :, :4].any()        # columns 0..3 see only zero base inputs
+    np.testing.assert_array_equal(out["y"][:, :, :4], 0.0)
+
+
+# ---------------------------------------------------------------------------
+# P6: nesting in Delta, count consistency
+# ---------------------------------------------------------------------------
+def test_fired_sets_nest_as_delta_grows():
+    rng = np.random.default_rng(21)
+    x, wb, wc = rand_problem(rng, 2, 9, 9, 8, 16, 4)
+    mean, var = rng.standard_normal(16) * 0.1, rng.uniform(0.5, 1.5, 16)
+    prev = None
+    fired = []
+    for dl in (-2.0, -0.5, 0.0, 0.7, 1.5, 4.0):
+        out = O.forward_float(x, wb, wc, gate_mean=mean, gate_var=var, delta=np.full(16, dl), epilogue=0)
+        if prev is not None:
+            assert not (out["d"] & ~prev).any()
+        prev = out["d"]
+        fired.append(out["fired"])
+        assert out["fired"] == int(out["d"].sum()) == int(out["counts"][2:].sum())
+    assert fired == sorted(fired, reverse=True) and fired[0] > fired[-1]
+
+
+def test_two_sided_gate():
+    # theta(Delta_h - z) * theta(z - Delta_l): both ends inclusive
+    x = np.ones((1, 3, 3, 2))
+    wb = np.ones((1, 3, 3, 1))
+    wc = np.ones((1, 3, 3, 1))
+    out = O.forward_float(x, wb, wc, gate_mean=[0.0], gate_var=[1.0], delta=[5.0], delta_hi=[6.0], epilogue=0)
+    assert out["d"].reshape(3, 3).tolist() == [[0, 1, 0], [1, 0, 1], [0, 1, 0]]
+    out = O.forward_float(x, wb, wc, gate_mean=[0.0], gate_var=[1.0], delta=[-np.inf], delta_hi=[4.0], epilogue=0)
+    assert out["d"].reshape(3, 3).tolist() == [[1, 0, 1], [0, 0, 0], [1, 0, 1]]
+    out = O.forward_float(x, wb, wc, gate_mean=[0.0], gate_var=[1.0], delta=[5.0], delta_hi=[np.inf], epilogue=0)
+    assert out["d"].sum() == 5
+
+
+# ---------------------------------------------------------------------------
+# epilogue: branch-specific scale/shift, residual, ReLU
+# ---------------------------------------------------------------------------
+def test_float_epilogue_against_library_conv():
+    rng = np.random.default_rng(33)
+    n, h, w, c_in, c_out, g = 2, 6, 6, 8, 5, 2
+    x, wb, wc = rand_problem(rng, n, h, w, c_in, c_out, g, ints=True)
+    P = lib_conv(x[..., :4], wb, 1, 1)
+    R = lib_conv(x[..., 4:], wc, 1, 1)
+    sc0, sh0 = rng.uniform(0.5, 1.5, c_out), rng.standard_normal(c_out)
+    sc1, sh1 = rng.uniform(0.5, 1.5, c_out), rng.standard_normal(c_out)
+    res = rng.standard_normal(P.shape)
+    mean = np.round(P.reshape(-1, c_out).mean(0))
+    out = O.forward_float(x, wb, wc, gate_mean=mean, gate_var=np.ones(c_out), delta=np.full(c_out, 0.5),
+                          scale0=sc0, shift0=sh0, scale1=sc1, shift1=sh1, residual=res,
+                          epilogue=O.RELU | O.AFFINE | O.RESIDUAL)
+    d = (P - mean) >= 0.5
+    want = np.where(d, sc1 * (P + R) + sh1, sc0 * P + sh0) + res
+    np.testing.assert_allclose(out["y"], np.maximum(want, 0), rtol=1e-14, atol=1e-12)
+    oth = np.where(~d, sc1 * (P + R) + sh1, sc0 * P + sh0) + res
+    np.testing.assert_allclose(out["y_other"], np.maximum(oth, 0), rtol=1e-14, atol=1e-12)
+    assert (out["y"] >= 0).all() and (out["y"] == 0).any()
+    # flags off: the same call returns the bare sum
+    bare = O.forward_float(x, wb, wc, gate_mean=mean, gate_var=np.ones(c_out), delta=np.full(c_out, 0.5),
+                           scale0=sc0, shift0=sh0, scale1=sc1, shift1=sh1, residual=res, epilogue=0)
+    np.testing.assert_array_equal(bare["y"], P + d * R)
+
+
+@pytest.mark.parametrize("acc,mult,bias,shift,relu,want", [
+    (3, 1, 0, 1, False, 2),        # 1.5 rounds half up
+    (-3, 1, 0, 1, False, -1),      # -1.5 rounds half up (towards +inf)
+    (-5, 1, 0, 1, False, -2),      # -2.5 -> -2
+    (5, 3, 0, 2, False, 4),        # 15/4 = 3.75 -> 4
+    (5, 3, 1, 2, False, 5),        # bias is added in output units
+    (100, 5, 0, 1, False, 127),    # clamp high
+    (-100, 5, 0, 1, False, -128),  # clamp low
+    (-100, 5, 0, 1, True, 0),      # ReLU clamps at zero instead
+    (7, 9, -2, 0, False, 61),      # shift 0: no rounding term
+])
+def test_int8_requant_closed_forms(acc, mult, bias, shift, relu, want):
+    # 1x1 layer, one pixel: the base sum is x*w = acc exactly; gate never fires (branch 0)
+    sign = 1 if acc >= 0 else -1
+    x = np.array([[[[abs(acc) if abs(acc) <= 127 else 100, 1]]]], np.int8)
+    wv = sign if abs(acc) <= 127 else sign * (abs(acc) // 100)
+    wb = np.array([[[[wv]]]], np.int8)
+    wc = np.array([[[[50]]]], np.int8)
+    out = O.forward_int8(x, wb, wc, np.array([2 ** 31 - 1], np.int32), pad=0, out_i8=True,
+                         rq_mult0=np.array([mult], np.int32), rq_mult1=np.array([1], np.int32),
+                         rq_bias=np.array([bias], np.int32), rq_shift=shift,
+                         epilogue=O.RELU if relu else 0)
+    assert int(out["P"].reshape(-1)[0]) == acc
+    assert int(out["y"].reshape(-1)[0]) == want
+
+
+def test_int8_requant_branches_and_residual():
+    rng = np.random.default_rng(8)
+    n, h, w, c_in, c_out, cb = 1, 5, 5, 8, 6, 2
+    x = rng.integers(0, 128, (n, h, w, c_in)).astype(np.int8)
+    wb = rng.integers(-127, 128, (c_out, 3, 3, cb)).astype(np.int8)
+    wc = rng.integers(-127, 128, (c_out, 3, 3, c_in - cb)).astype(np.int8)
+    P = np.rint(lib_conv(x[..., :cb], wb, 1, 1)).astype(np.int64)
+    R = np.rint(lib_conv(x[..., cb:], wc, 1, 1)).astype(np.int64)
+    thr = np.median(P.reshape(-1, c_out), axis=0).astype(np.int32)
+    m0 = rng.integers(1, 400, c_out).astype(np.int32)
+    m1 = rng.integers(1, 400, c_out).astype(np.int32)
+    bias = rng.integers(-20, 20, c_out).astype(np.int32)
+    res = rng.integers(-128, 128, P.shape).astype(np.int8)
+    shift, rmul = 14, 9000
+    out = O.forward_int8(x, wb, wc, thr, out_i8=True, rq_mult0=m0, rq_mult1=m1, rq_bias=bias, rq_shift=shift,
+                         residual=res, rq_res_mult=rmul, epilogue=O.RESIDUAL)
+    d = P >= thr
+    t = np.where(d, (P + R) * m1, P * m0) + bias.astype(np.int64) * (1 << shift) + res.astype(np.int64) * rmul
+    want = np.clip(np.floor_divide(t + (1 << (shift - 1)), 1 << shift), -128, 127)
+    assert np.array_equal(out["y"], want)
+    assert np.array_equal(out["d"], d.astype(np.uint8))
+    assert 0 < d.mean() < 1 and (want == 127).any() and (want > -128).any()
+    # raw int32 output: S (+ residual*mult) with optional ReLU
+    raw = O.forward_int8(x, wb, wc, thr, residual=res, rq_res_mult=3, epilogue=O.RESIDUAL | O.RELU)
+    assert np.array_equal(raw["y"], np.maximum(P + d * R + 3 * res.astype(np.int64), 0))
+
+
+def test_rejects_bad_problems():
+    x = np.ones((1, 3, 3, 2))
+    with pytest.raises(ValueError):
+        O.forward_float(x, np.ones((1, 3, 3, 1)), np.ones((1, 3, 3, 1)))   # gated but no statistics
