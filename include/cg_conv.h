@@ -1,0 +1,152 @@
+/*
+ * cg_conv.h -- C ABI of the channel-gated convolution layer for AMD MI355X (gfx950).
+ *
+ * One layer of "Channel Gating Neural Networks" at inference time (paper Sec. 3.1,
+ * Eq. 1, and the merged normalise-and-compare gate of Sec. 3.2):
+ *
+ *     x = [x_p, x_r]   split along input channels, x_p = channels [0, c_base)
+ *     P = W_p * x_p                     base path, always evaluated
+ *     d = (P >= E + Delta*sqrt(Var+eps))  one binary decision per output activation
+ *                                         (Heaviside step: a tie fires)
+ *     S = P + d * (W_r * x_r)           conditional path only where d = 1
+ *     y = f_d(S)                        per-channel scale/shift chosen by d (the two
+ *                                       batch norms of Sec. 4 folded for inference),
+ *                                       optional residual add, optional ReLU
+ *
+ * "*" is cross-correlation with symmetric zero padding and floor output size:
+ *     Ho = (H + 2*pad - kh) / stride + 1,   Wo likewise.
+ *
+ * Layouts.  Activations are NHWC: x[n][h][w][c] with `x_pixel_stride` elements
+ * between pixels (>= c_in); y, residual: [n][ho][wo][c_out], dense.  Weights are
+ * [c_out][kh][kw][c] with c = c_base (w_base) or c_in - c_base (w_cond).
+ *
+ * Memory.  The library allocates no device memory.  Every device buffer (x, y,
+ * residual, bitmap, counts, workspace, `packed`, the weights) belongs to the caller
+ * and is passed as a raw device pointer; `hip_stream` is the caller's hipStream_t
+ * (NULL = the default stream).  Host arrays named in the descriptor are read during
+ * cg_conv_create only.  The handle is host memory owned by the library.
+ *
+ * Every entry point returns a status and never throws or aborts.  All argument
+ * checks happen before the first HIP call, so they behave the same on a host with
+ * no GPU.  cg_last_error() gives the text of the calling thread's last failure.
+ */
+#ifndef CG_CONV_H
+#define CG_CONV_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct cg_conv cg_conv; /* opaque */
+
+enum { CG_OK = 0, CG_EINVAL = 1, CG_EUNSUPPORTED = 2, CG_ENOMEM = 3, CG_EHIP = 4 };
+enum { CG_F32 = 0, CG_BF16 = 1, CG_I8 = 2, CG_I32 = 3 };
+enum { CG_EPI_RELU = 1u, CG_EPI_AFFINE = 2u, CG_EPI_RESIDUAL = 4u };
+/* Kernel family.  AUTO picks the matrix-core kernels when the shape allows and the
+ * plain one-thread-per-activation kernel otherwise. */
+enum { CG_VARIANT_AUTO = 0, CG_VARIANT_NAIVE = 1, CG_VARIANT_MFMA = 2 };
+
+typedef struct cg_conv_desc {
+  uint32_t struct_size;      /* = sizeof(cg_conv_desc); checked */
+  int32_t n_max;             /* largest batch a forward call may pass */
+  int32_t h, w, c_in, c_out; /* input height, width, channels; output channels */
+  int32_t kh, kw;            /* kernel size: 3x3 or 1x1 */
+  int32_t stride, pad;       /* stride >= 1, pad >= 0 */
+  int32_t c_base;            /* base-path channels, C_in/G (Sec. 3.1: eta*c_l).
+                                c_base == c_in: plain dense convolution, no gate */
+  int32_t in_dtype;          /* x, W: CG_F32 | CG_BF16 | CG_I8 */
+  int32_t out_dtype;         /* y, residual.  float inputs: CG_F32 | CG_BF16;
+                                CG_I8 inputs: CG_I32 (raw sum) | CG_I8 (requantised) */
+  uint32_t epilogue;         /* CG_EPI_* flags */
+  int32_t variant;           /* CG_VARIANT_* */
+  int32_t reserved0;
+  int64_t x_pixel_stride;    /* elements between pixels of x; 0 means c_in */
+
+  const void* w_base;        /* DEVICE [c_out][kh][kw][c_base] */
+  const void* w_cond;        /* DEVICE [c_out][kh][kw][c_in-c_base]; NULL iff dense */
+
+  /* Gate, float inputs (HOST, [c_out]): fires iff P >= mean + delta*sqrt(var+eps).
+   * delta = -inf always fires, +inf never fires.  delta_hi (nullable) adds the upper
+   * threshold of the two-sided gate for saturating activations (Sec. 3.2):
+   * fires iff also P <= mean + delta_hi*sqrt(var+eps). */
+  const float* gate_mean;
+  const float* gate_var;
+  const float* delta;
+  const float* delta_hi;
+  float gate_eps;
+  int32_t reserved1;
+  /* Gate, CG_I8 inputs (HOST, [c_out]): fires iff the int32 base sum >= thr. */
+  const int32_t* gate_thr_i32;
+
+  /* Epilogue, float (HOST, [c_out], each nullable = 1 / 0): y = scale_d*S + shift_d. */
+  const float* scale0;
+  const float* shift0;
+  const float* scale1;
+  const float* shift1;
+  /* Epilogue, CG_I8 -> CG_I8 (HOST, [c_out], nullable = 1 / 1 / 0):
+   *   t = S*mult_d + (bias << shift) + residual*res_mult;
+   *   y = clamp((t + (1 << (shift-1))) >> shift, RELU ? 0 : -128, 127)   (arithmetic shift)
+   * CG_I8 -> CG_I32: y = S + residual*res_mult, ReLU if asked. */
+  const int32_t* rq_mult0;
+  const int32_t* rq_mult1;
+  const int32_t* rq_bias;
+  int32_t rq_shift;          /* 0..31 */
+  int32_t rq_res_mult;
+
+  void* packed;              /* DEVICE, >= cg_conv_packed_bytes(desc), 256-byte aligned, caller-owned;
+                                must outlive the handle; holds repacked weights and per-channel tables */
+  size_t packed_bytes;
+} cg_conv_desc;
+
+/* Bytes the caller must provide in desc->packed; 0 if the descriptor is invalid
+ * (cg_last_error says why). */
+size_t cg_conv_packed_bytes(const cg_conv_desc* desc);
+
+/* Validates the descriptor, folds the gate statistics into one threshold per output
+ * channel (Sec. 3.2), and enqueues on `hip_stream` the copies/kernels that fill
+ * desc->packed from w_base / w_cond and the host tables.  Work that uses the handle
+ * must be ordered after that stream's work.  On failure *out is NULL. */
+int cg_conv_create(cg_conv** out, const cg_conv_desc* desc, void* hip_stream);
+
+/* Device scratch a forward call of batch n needs (may be 0). */
+size_t cg_conv_workspace_bytes(const cg_conv* h, int32_t n);
+
+/*
+ * Enqueues one forward pass of the layer (Eq. 1) for a batch of n <= n_max images on
+ * `hip_stream` and returns without waiting.  All pointers are DEVICE pointers.
+ *   x         [n][h][w] pixels of x_pixel_stride elements, in_dtype
+ *   residual  [n][ho][wo][c_out]; out_dtype for float inputs, int8 for CG_I8 inputs;
+ *             required iff CG_EPI_RESIDUAL
+ *   y         [n][ho][wo][c_out] out_dtype
+ *   bitmap    nullable.  Decisions, one bit per output activation: row m = (n*Ho+ho)*Wo+wo has
+ *             ceil(c_out/32) words; bit (co & 31) of word (co >> 5) is d[m][co]; unused bits 0.
+ *             A dense layer (c_base == c_in) writes zeros.
+ *   counts    nullable, 8-byte aligned.  2 + n*c_out words, fully overwritten: words 0,1 = number of fired gates
+ *             (low, high half of a 64-bit count); word 2 + img*c_out + co = fired gates of that
+ *             image and output channel (the sum the channel-wise gate of Sec. 3.2 thresholds).
+ *   workspace >= cg_conv_workspace_bytes(h, n) bytes, 256-byte aligned; may be NULL if that is 0.
+ * Calls on one handle may overlap only if they use distinct y / bitmap / counts / workspace.
+ * Errors: CG_EINVAL (NULL where not allowed, n out of range, workspace too small),
+ * CG_EHIP (a launch failed).
+ */
+int cg_conv_forward(cg_conv* h, int32_t n, const void* x, const void* residual, void* y,
+                    uint32_t* bitmap, uint32_t* counts, void* workspace, size_t workspace_bytes,
+                    void* hip_stream);
+
+/* Frees the host handle; touches no device memory.  NULL is a no-op. */
+void cg_conv_destroy(cg_conv* h);
+
+/* Output geometry of a handle: writes Ho, Wo; returns the kernel family in use (CG_VARIANT_*),
+ * or -1 for a NULL handle. */
+int cg_conv_info(const cg_conv* h, int32_t* ho, int32_t* wo);
+
+/* Text of the calling thread's most recent error; never NULL. */
+const char* cg_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CG_CONV_H */
