@@ -14,12 +14,34 @@ from typing import Optional
 
 import numpy as np
 
+# The PyTorch wheel ships its own HIP runtime (soname libamdhip64.so.7).  The library and
+# torch must share ONE runtime or the second one finds no device, so torch is imported
+# first: the loader then resolves libcg_conv.so's libamdhip64.so.7 to the copy already mapped.
+import torch  # noqa: F401,E402
+
 _LIB_PATH = Path(__file__).resolve().parent / "libcg_conv.so"
 if not _LIB_PATH.exists():
     raise ImportError(
         "%s is missing: build the HIP library first (python paper_1805_12549_amd/build.py or "
         "__graft_entry__.build()); there is no fallback path" % _LIB_PATH)
 _lib = C.CDLL(str(_LIB_PATH))
+
+
+def _hip_runtimes_mapped():
+    seen = set()
+    try:
+        with open("/proc/self/maps") as f:
+            for line in f:
+                if "libamdhip64" in line:
+                    seen.add(line.split()[-1])
+    except OSError:
+        pass
+    return sorted(seen)
+
+
+if len(_hip_runtimes_mapped()) > 1:
+    raise ImportError("two HIP runtimes are mapped into this process (%s); import torch before anything "
+                      "that loads libamdhip64" % ", ".join(_hip_runtimes_mapped()))
 
 CG_OK, CG_EINVAL, CG_EUNSUPPORTED, CG_ENOMEM, CG_EHIP = 0, 1, 2, 3, 4
 CG_F32, CG_BF16, CG_I8, CG_I32 = 0, 1, 2, 3
