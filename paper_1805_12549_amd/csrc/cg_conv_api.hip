@@ -4,6 +4,7 @@
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <limits>
 #include <new>
@@ -176,6 +177,13 @@ int cg_conv_create(cg_conv** out, const cg_conv_desc* desc, void* hip_stream) {
   rc = resolve_variant(d, plan, &variant);
   if (rc != CG_OK) return rc;
   const Layout lay = make_layout(d, plan, variant == CG_VARIANT_MFMA);
+  if (getenv("CG_DEBUG"))
+    fprintf(stderr,
+            "[cg_conv] variant=%d plan.ok=%d bn=%d n_cb=%d tr=%d ti=%d tiles/img=%d patch=%dx%d npix=%d bm=%d ng=%d "
+            "cbq=%d,%d stages=%d,%d steps=%d,%d ps=%d,%d lds=%d packed=%zu\n",
+            variant, plan.ok, plan.bn, plan.n_cb, plan.tr, plan.ti, plan.tiles_per_img, plan.pr, plan.pwid, plan.npix,
+            plan.bm_valid, plan.ng, plan.cbq[0], plan.cbq[1], plan.stages[0], plan.stages[1], plan.tsteps[0],
+            plan.tsteps[1], plan.ps[0], plan.ps[1], plan.lds_total, lay.total);
   if (!d.packed) return fail(CG_EINVAL, "packed is NULL");
   if (((uintptr_t)d.packed & 255) != 0) return fail(CG_EINVAL, "packed must be 256-byte aligned");
   if (d.packed_bytes < lay.total)
@@ -289,6 +297,9 @@ int cg_conv_forward(cg_conv* h, int32_t n, const void* x, const void* residual, 
   if ((h->d.epilogue & CG_EPI_RESIDUAL) && !residual)
     return fail(CG_EINVAL, "residual is NULL but the layer was created with CG_EPI_RESIDUAL");
   if (counts && ((uintptr_t)counts & 7)) return fail(CG_EINVAL, "counts must be 8-byte aligned");
+  if (h->variant == CG_VARIANT_MFMA &&
+      ((((uintptr_t)x) | ((uintptr_t)y) | ((uintptr_t)residual) | ((uintptr_t)bitmap)) & 15))
+    return fail(CG_EINVAL, "x, y, residual and bitmap must be 16-byte aligned");
   const size_t need = cg_conv_workspace_bytes(h, n);
   if (need > 0 && (!workspace || workspace_bytes < need))
     return fail(CG_EINVAL, "workspace of %zu bytes is smaller than the %zu required", workspace_bytes, need);

@@ -41,13 +41,32 @@ struct Params {
   uint32_t* counts;
 };
 
-// Repacked-weight geometry of the matrix-core kernels (filled by mfma_plan).
+// Geometry of the matrix-core kernels for one layer (host-computed, passed by value).
+//
+// A workgroup owns a tile of up to 128 output pixels (`ti` whole images or `tr` output
+// rows of one image) times BN output channels.  The input patch those pixels read is
+// staged in LDS once per K stage, `cbq` 16-byte channel chunks per pixel at a time,
+// together with the matching slice of prepacked weights.  Phase 0 is the base path
+// (channels [0,c_base)), phase 1 the conditional path.
 struct MfmaPlan {
-  int ok;                // 0: shape not supported by the matrix-core kernels
-  int elem_bytes;        // 2 (bf16) or 1 (int8)
-  int chunk;             // channels per 16-byte chunk: 8 (bf16) or 16 (int8)
-  int bm, bn;            // workgroup tile: output pixels x output channels
-  int kq_base, kq_cond;  // K extent in 16-byte chunks, padded to a multiple of 4 (one MFMA step)
+  int ok;                  // 0: shape not covered by the matrix-core kernels
+  int elem_bytes;          // 2 (bf16) or 1 (int8)
+  int ch;                  // channels per 16-byte chunk: 8 (bf16) or 16 (int8)
+  int bn;                  // output channels per workgroup (64 or 128)
+  int n_cb;                // c_out / bn
+  int tr, ti;              // output rows per tile / images per tile (ti > 1 only with tr == ho)
+  int tiles_per_img;       // ceil(ho / tr) when ti == 1
+  int pr, pwid, npix;      // patch rows, patch width, patch pixels = ti*pr*pwid
+  int bm_valid;            // ti*tr*wo output pixels per full tile (<= 128)
+  int ng;                  // 16-pixel row groups per tile = ceil(bm_valid / 16)
+  int taps;                // kh*kw
+  int cbq[2];              // 16-byte chunks per pixel per stage
+  int stages[2];           // K stages per phase (0 for an absent phase)
+  int tsteps[2];           // MFMA K steps per stage = ceil(taps*cbq / 4)
+  int ps[2];               // LDS bytes per patch pixel (odd multiple of 16: conflict-free reads)
+  // LDS byte offsets
+  int lds_aoff, lds_gidx, lds_outpp, lds_outm, lds_colcnt, lds_dbits, lds_stage, lds_w[2], lds_total;
+  size_t wpk_stage_bytes[2];  // bytes of one (column block, stage) slice of prepacked weights
   size_t wpk_base_bytes, wpk_cond_bytes;
 };
 
