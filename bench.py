@@ -39,6 +39,8 @@ def parse():
     ap.add_argument("--no-dense", action="store_true", help="skip the dense comparator (for kernel profiles)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline")
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying a HIP graph")
+    ap.add_argument("--variant", default="auto", choices=["auto", "blockskip", "compact"],
+                    help="kernel family (auto = what the library picks)")
     ap.add_argument("--layers", default="", help="comma-separated layer names to restrict the workload")
     return ap.parse_args()
 
@@ -59,6 +61,7 @@ def main():
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
 
+    variant = {"auto": B.CG_VARIANT_AUTO, "blockskip": B.CG_VARIANT_MFMA, "compact": B.CG_VARIANT_MFMA_COMPACT}[args.variant]
     shapes = W.imagenet_shapes(n=args.batch)
     if args.layers:
         keep = set(args.layers.split(","))
@@ -79,7 +82,7 @@ def main():
         wc = torch.from_numpy(inp.w_cond).to(dev).to(torch.bfloat16)
         wfull = torch.cat([wb, wc], dim=-1).contiguous()
         common = dict(n_max=s.n, h=s.h, w=s.w, c_in=s.c_in, c_out=s.c_out, in_dtype=B.CG_BF16, out_dtype=B.CG_BF16,
-                      stride=s.stride, pad=s.pad, epilogue=B.CG_EPI_RELU, variant=B.CG_VARIANT_MFMA)
+                      stride=s.stride, pad=s.pad, epilogue=B.CG_EPI_RELU, variant=variant)
         gated = B.GatedConv(c_base=s.c_base, w_base=wb, w_cond=wc, gate_mean=gate.mean, gate_var=gate.var,
                             delta=gate.delta, **common)
         dense = None if args.no_dense else B.GatedConv(c_base=s.c_in, w_base=wfull, w_cond=None, **common)
@@ -194,7 +197,9 @@ def main():
             traffic = None
     roofline = dict(bound="mfma", achieved=round(achieved, 2), peak=PEAK_BF16_TFLOPS, unit="TFLOP/s",
                     frac=round(achieved / PEAK_BF16_TFLOPS, 4), traffic=traffic,
-                    kernel="gated_conv_mfma_kernel<bf16>", avg_launch_us=round(t_kernel_us / len(layers), 2),
+                    kernel={B.CG_VARIANT_MFMA: "gated_conv_mfma_kernel<bf16>",
+                            B.CG_VARIANT_MFMA_COMPACT: "gated_conv_compact_kernel<bf16>"}.get(
+                                layers[0]["gated"].variant, "naive_kernel"), avg_launch_us=round(t_kernel_us / len(layers), 2),
                     algorithmic_gflop_per_launch=round(alg_flops / len(layers) / 1e9, 3),
                     hbm_gbs_algorithmic=round(alg_bytes / (t_kernel_us * 1e-6) / 1e9, 1),
                     hbm_frac=round(alg_bytes / (t_kernel_us * 1e-6) / 1e9 / PEAK_HBM_GBS, 4))

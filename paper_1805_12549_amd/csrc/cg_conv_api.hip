@@ -56,6 +56,7 @@ struct cg_conv {
   int ho, wo, c_cond;
   int variant;              // resolved CG_VARIANT_*
   cg::MfmaPlan plan;
+  cg::Mfma2Plan plan2;
   Layout lay;
   std::vector<uint32_t> staging;  // host image of the tables; kept alive for the async copy
 };
@@ -85,7 +86,8 @@ int validate(const cg_conv_desc* d, int* ho, int* wo) {
     return fail(CG_EINVAL, "float inputs need out_dtype CG_F32 or CG_BF16");
   }
   if (d->epilogue & ~(CG_EPI_RELU | CG_EPI_AFFINE | CG_EPI_RESIDUAL)) return fail(CG_EINVAL, "unknown epilogue flag");
-  if (d->variant != CG_VARIANT_AUTO && d->variant != CG_VARIANT_NAIVE && d->variant != CG_VARIANT_MFMA)
+  if (d->variant != CG_VARIANT_AUTO && d->variant != CG_VARIANT_NAIVE && d->variant != CG_VARIANT_MFMA &&
+      d->variant != CG_VARIANT_MFMA_COMPACT)
     return fail(CG_EINVAL, "unknown variant %d", d->variant);
   if (d->x_pixel_stride != 0 && d->x_pixel_stride < d->c_in)
     return fail(CG_EINVAL, "x_pixel_stride must be 0 or >= c_in");
@@ -119,7 +121,7 @@ int validate(const cg_conv_desc* d, int* ho, int* wo) {
   return CG_OK;
 }
 
-Layout make_layout(const cg_conv_desc& d, const cg::MfmaPlan& plan, bool use_mfma) {
+Layout make_layout(const cg_conv_desc& d, size_t wpk_base_bytes, size_t wpk_cond_bytes) {
   Layout l{};
   const size_t eb = (size_t)elem_bytes(d.in_dtype);
   const size_t taps = (size_t)d.kh * d.kw;
@@ -132,17 +134,32 @@ Layout make_layout(const cg_conv_desc& d, const cg::MfmaPlan& plan, bool use_mfm
   l.w_cond_off = off;
   off += align256(l.w_cond_bytes);
   l.wpk_base_off = off;
-  if (use_mfma) off += align256(plan.wpk_base_bytes);
+  off += align256(wpk_base_bytes);
   l.wpk_cond_off = off;
-  if (use_mfma) off += align256(plan.wpk_cond_bytes);
+  off += align256(wpk_cond_bytes);
   l.total = off;
   return l;
 }
 
-int resolve_variant(const cg_conv_desc& d, const cg::MfmaPlan& plan, int* variant) {
-  if (d.variant == CG_VARIANT_MFMA && !plan.ok)
-    return fail(CG_EUNSUPPORTED, "the matrix-core kernels do not cover this shape/dtype");
-  *variant = (d.variant == CG_VARIANT_NAIVE || !plan.ok) ? CG_VARIANT_NAIVE : CG_VARIANT_MFMA;
+struct Plans {
+  cg::MfmaPlan v1;
+  cg::Mfma2Plan v2;
+  int variant;
+  size_t wpk_base_bytes, wpk_cond_bytes;
+};
+
+int resolve_variant(const cg_conv_desc& d, Plans* pl) {
+  pl->v1 = cg::mfma_plan(d);
+  pl->v2 = cg::mfma2_plan(d);
+  if (d.variant == CG_VARIANT_MFMA && !pl->v1.ok)
+    return fail(CG_EUNSUPPORTED, "the block-skipping matrix-core kernel does not cover this shape/dtype");
+  if (d.variant == CG_VARIANT_MFMA_COMPACT && !pl->v2.ok)
+    return fail(CG_EUNSUPPORTED, "the pixel-compacting matrix-core kernel does not cover this shape/dtype");
+  int v = d.variant;
+  if (v == CG_VARIANT_AUTO) v = pl->v2.ok ? CG_VARIANT_MFMA_COMPACT : pl->v1.ok ? CG_VARIANT_MFMA : CG_VARIANT_NAIVE;
+  pl->variant = v;
+  pl->wpk_base_bytes = v == CG_VARIANT_MFMA_COMPACT ? pl->v2.wpk_base_bytes : v == CG_VARIANT_MFMA ? pl->v1.wpk_base_bytes : 0;
+  pl->wpk_cond_bytes = v == CG_VARIANT_MFMA_COMPACT ? pl->v2.wpk_cond_bytes : v == CG_VARIANT_MFMA ? pl->v1.wpk_cond_bytes : 0;
   return CG_OK;
 }
 
@@ -159,24 +176,27 @@ extern "C" {
 const char* cg_last_error(void) { return g_err.c_str(); }
 
 size_t cg_conv_packed_bytes(const cg_conv_desc* desc) {
-  int ho, wo, variant;
+  int ho, wo;
   if (validate(desc, &ho, &wo) != CG_OK) return 0;
-  const cg::MfmaPlan plan = cg::mfma_plan(*desc);
-  if (resolve_variant(*desc, plan, &variant) != CG_OK) return 0;
-  return make_layout(*desc, plan, variant == CG_VARIANT_MFMA).total;
+  Plans pl;
+  if (resolve_variant(*desc, &pl) != CG_OK) return 0;
+  return make_layout(*desc, pl.wpk_base_bytes, pl.wpk_cond_bytes).total;
 }
 
 int cg_conv_create(cg_conv** out, const cg_conv_desc* desc, void* hip_stream) {
   if (!out) return fail(CG_EINVAL, "out is NULL");
   *out = nullptr;
-  int ho, wo, variant;
+  int ho, wo;
   int rc = validate(desc, &ho, &wo);
   if (rc != CG_OK) return rc;
   const cg_conv_desc& d = *desc;
-  const cg::MfmaPlan plan = cg::mfma_plan(d);
-  rc = resolve_variant(d, plan, &variant);
+  Plans pl;
+  rc = resolve_variant(d, &pl);
   if (rc != CG_OK) return rc;
-  const Layout lay = make_layout(d, plan, variant == CG_VARIANT_MFMA);
+  const int variant = pl.variant;
+  const cg::MfmaPlan& plan = pl.v1;
+  const cg::Mfma2Plan& plan2 = pl.v2;
+  const Layout lay = make_layout(d, pl.wpk_base_bytes, pl.wpk_cond_bytes);
   if (getenv("CG_DEBUG"))
     fprintf(stderr,
             "[cg_conv] variant=%d plan.ok=%d bn=%d n_cb=%d tr=%d ti=%d tiles/img=%d patch=%dx%d npix=%d bm=%d ng=%d "
@@ -184,6 +204,13 @@ int cg_conv_create(cg_conv** out, const cg_conv_desc* desc, void* hip_stream) {
             variant, plan.ok, plan.bn, plan.n_cb, plan.tr, plan.ti, plan.tiles_per_img, plan.pr, plan.pwid, plan.npix,
             plan.bm_valid, plan.ng, plan.cbq[0], plan.cbq[1], plan.stages[0], plan.stages[1], plan.tsteps[0],
             plan.tsteps[1], plan.ps[0], plan.ps[1], plan.lds_total, lay.total);
+  if (getenv("CG_DEBUG") && plan2.ok)
+    fprintf(stderr,
+            "[cg_conv] compact plan: ngw=%d bm=%d n_cb=%d tr=%d patch=%dx%d npix=%d bm_valid=%d ng=%d max_imgs=%d cbq=%d "
+            "stages=%d,%d steps=%d kp=%d stage_bytes=%d lds=%d\n",
+            plan2.ngw, plan2.bm, plan2.n_cb, plan2.tr, plan2.pr_max, plan2.pw, plan2.npix, plan2.bm_valid, plan2.ng,
+            plan2.max_imgs, plan2.cbq, plan2.stages[0], plan2.stages[1], plan2.tsteps, plan2.kp, plan2.stage_bytes,
+            plan2.lds_total);
   if (!d.packed) return fail(CG_EINVAL, "packed is NULL");
   if (((uintptr_t)d.packed & 255) != 0) return fail(CG_EINVAL, "packed must be 256-byte aligned");
   if (d.packed_bytes < lay.total)
@@ -198,6 +225,7 @@ int cg_conv_create(cg_conv** out, const cg_conv_desc* desc, void* hip_stream) {
   h->c_cond = d.c_in - d.c_base;
   h->variant = variant;
   h->plan = plan;
+  h->plan2 = plan2;
   h->lay = lay;
 
   // Host image of the per-channel tables.
@@ -252,7 +280,7 @@ int cg_conv_create(cg_conv** out, const cg_conv_desc* desc, void* hip_stream) {
     e = hipMemcpyAsync(pk + lay.w_base_off, d.w_base, lay.w_base_bytes, hipMemcpyDeviceToDevice, s);
   if (e == hipSuccess && lay.w_cond_bytes)
     e = hipMemcpyAsync(pk + lay.w_cond_off, d.w_cond, lay.w_cond_bytes, hipMemcpyDeviceToDevice, s);
-  if (e == hipSuccess && variant == CG_VARIANT_MFMA) {
+  if (e == hipSuccess && (variant == CG_VARIANT_MFMA || variant == CG_VARIANT_MFMA_COMPACT)) {
     cg::Params p{};
     p.c_in = d.c_in;
     p.c_out = d.c_out;
@@ -263,7 +291,10 @@ int cg_conv_create(cg_conv** out, const cg_conv_desc* desc, void* hip_stream) {
     p.in_dtype = d.in_dtype;
     p.w_base = pk + lay.w_base_off;
     p.w_cond = pk + lay.w_cond_off;
-    e = cg::launch_mfma_pack(plan, p, pk + lay.wpk_base_off, pk + lay.wpk_cond_off, s);
+    if (variant == CG_VARIANT_MFMA)
+      e = cg::launch_mfma_pack(plan, p, pk + lay.wpk_base_off, pk + lay.wpk_cond_off, s);
+    else
+      e = cg::launch_mfma2_pack(plan2, p, pk + lay.wpk_base_off, pk + lay.wpk_cond_off, s);
   }
   if (e != hipSuccess) {
     const int code = fail(CG_EHIP, "cg_conv_create: %s", hipGetErrorString(e));
@@ -297,7 +328,7 @@ int cg_conv_forward(cg_conv* h, int32_t n, const void* x, const void* residual, 
   if ((h->d.epilogue & CG_EPI_RESIDUAL) && !residual)
     return fail(CG_EINVAL, "residual is NULL but the layer was created with CG_EPI_RESIDUAL");
   if (counts && ((uintptr_t)counts & 7)) return fail(CG_EINVAL, "counts must be 8-byte aligned");
-  if (h->variant == CG_VARIANT_MFMA &&
+  if (h->variant != CG_VARIANT_NAIVE &&
       ((((uintptr_t)x) | ((uintptr_t)y) | ((uintptr_t)residual) | ((uintptr_t)bitmap)) & 15))
     return fail(CG_EINVAL, "x, y, residual and bitmap must be 16-byte aligned");
   const size_t need = cg_conv_workspace_bytes(h, n);
@@ -330,6 +361,7 @@ int cg_conv_forward(cg_conv* h, int32_t n, const void* x, const void* residual, 
   p.rq_shift = d.rq_shift;
   p.rq_res_mult = d.rq_res_mult;
   p.words = (d.c_out + 31) / 32;
+  { const char* dbg = getenv("CG_DEBUG_SKIP"); p.debug = dbg ? atoi(dbg) : 0; }
   const size_t ts = l.table_stride;
   p.thr_f = (const float*)(pk + 0 * ts);
   p.thr_hi_f = (const float*)(pk + 1 * ts);
@@ -353,7 +385,9 @@ int cg_conv_forward(cg_conv* h, int32_t n, const void* x, const void* residual, 
   hipError_t e = hipSuccess;
   if (counts) e = cg::launch_zero_u32(counts, 2 + (size_t)n * d.c_out, s);
   if (e == hipSuccess) {
-    if (h->variant == CG_VARIANT_MFMA)
+    if (h->variant == CG_VARIANT_MFMA_COMPACT)
+      e = cg::launch_mfma2(h->plan2, p, pk + l.wpk_base_off, pk + l.wpk_cond_off, s);
+    else if (h->variant == CG_VARIANT_MFMA)
       e = cg::launch_mfma(h->plan, p, pk + l.wpk_base_off, pk + l.wpk_cond_off, s);
     else
       e = cg::launch_naive(p, s);

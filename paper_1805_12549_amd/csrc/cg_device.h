@@ -8,13 +8,8 @@ namespace cg {
 
 __device__ __forceinline__ float bf16_to_float(uint16_t b) { return __uint_as_float(((uint32_t)b) << 16); }
 
-// round to nearest even; NaN stays NaN
-__device__ __forceinline__ uint16_t float_to_bf16(float f) {
-  uint32_t u = __float_as_uint(f);
-  if ((u & 0x7fffffffu) > 0x7f800000u) return 0x7fc0;
-  u += 0x7fffu + ((u >> 16) & 1u);
-  return (uint16_t)(u >> 16);
-}
+// round to nearest even; NaN stays NaN (gfx950 converts in hardware: v_cvt_pk_bf16_f32)
+__device__ __forceinline__ uint16_t float_to_bf16(float f) { return __builtin_bit_cast(uint16_t, (__bf16)f); }
 
 __device__ __forceinline__ float load_as_float(const void* p, long long i, int dtype) {
   return dtype == CG_F32 ? ((const float*)p)[i] : bf16_to_float(((const uint16_t*)p)[i]);

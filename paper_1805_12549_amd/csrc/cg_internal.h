@@ -21,6 +21,7 @@ struct Params {
   int gated;               // 0: dense layer, no gate, second affine pair applies
   int rq_shift, rq_res_mult;
   int words;               // bitmap words per pixel = ceil(c_out/32)
+  int debug;               // profiling knobs (CG_DEBUG_SKIP): results are wrong when non-zero
 
   // per-output-channel tables, device, in `packed`
   const float* thr_f;      // lower threshold on the fp32 base sum (Sec. 3.2 merged gate)
@@ -71,6 +72,40 @@ struct MfmaPlan {
 };
 
 MfmaPlan mfma_plan(const cg_conv_desc& d);
+
+// Geometry of the pixel-compacting matrix-core kernel.
+//
+// Output rows of the whole batch are numbered R = img*Ho + ho.  A workgroup owns `tr`
+// consecutive global rows (<= bm pixels, they may straddle images) x 64 output channels.
+// Input rows live in a "stacked padded" space, row = img*(H+2*pad) + hi + pad, in which the
+// rows a tile reads form one contiguous range even across an image boundary.
+struct Mfma2Plan {
+  int ok;
+  int elem_bytes, ch;      // bytes per element; channels per 16-byte chunk
+  int ngw;                 // 16-pixel row groups per wavefront in the base phase (2 or 4)
+  int bm;                  // ngw*64: pixels per tile, padded
+  int n_cb;                // c_out / 64
+  int tr;                  // global output rows per tile
+  int hp;                  // h + 2*pad
+  unsigned magic_hp, magic_ho, magic_wo;   // ceil(2^32 / d): exact division of 16-bit values by hp, ho, wo
+  int pr_max, pw, npix;    // patch rows (max over tiles), patch width, pr_max*pw
+  int bm_valid;            // tr*wo
+  int ng;                  // ceil(bm_valid/16)
+  int max_imgs;            // images one tile can touch
+  int cbq;                 // 16-byte channel chunks per pixel per K stage: 1, 2 or 4
+  int stages[2];           // K stages of the base / conditional phase
+  int tsteps;              // MFMA K steps per stage = ceil(9*cbq/4)
+  int kp;                  // patch chunks per thread per stage = ceil(npix*cbq/256)
+  int patch_bytes, w_bytes, stage_bytes;
+  int lds_goff, lds_outpp, lds_outm, lds_flag, lds_clist, lds_rank, lds_dbits, lds_colcnt, lds_zero, lds_misc,
+      lds_stage, lds_total;
+  size_t wpk_stage_bytes, wpk_base_bytes, wpk_cond_bytes;
+};
+
+Mfma2Plan mfma2_plan(const cg_conv_desc& d);
+hipError_t launch_mfma2_pack(const Mfma2Plan& plan, const Params& p, void* wpk_base, void* wpk_cond, hipStream_t s);
+hipError_t launch_mfma2(const Mfma2Plan& plan, const Params& p, const void* wpk_base, const void* wpk_cond,
+                        hipStream_t s);
 
 // launchers (return hipError_t from the last launch)
 hipError_t launch_naive(const Params& p, hipStream_t s);

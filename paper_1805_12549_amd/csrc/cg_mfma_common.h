@@ -1,0 +1,127 @@
+// Pieces shared by the matrix-core kernels: vector types, the bf16 / int8 MFMA traits and
+// the whole-row output function (f of Eq. 1 applied to eight consecutive channels).
+#pragma once
+
+#include "cg_device.h"
+
+namespace cg {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(4))) int i32x4;
+
+struct Bf16Traits {
+  using acc4 = f32x4;
+  using acc_t = float;
+  static constexpr int kDtype = CG_BF16;
+  // 16x16 output block, K = 32: lane l supplies row/column l%16 and the 8 elements
+  // (one 16-byte chunk) number l/16 of the K slice, for A and B alike.
+  static __device__ __forceinline__ acc4 mfma(i32x4 a, i32x4 b, acc4 c) {
+    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0,
+                                                   0, 0);
+  }
+  static __device__ __forceinline__ bool fires(float v, float lo, float hi) { return v >= lo && v <= hi; }
+};
+
+struct I8Traits {
+  using acc4 = i32x4;
+  using acc_t = int32_t;
+  static constexpr int kDtype = CG_I8;
+  static __device__ __forceinline__ acc4 mfma(i32x4 a, i32x4 b, acc4 c) {
+    return __builtin_amdgcn_mfma_i32_16x16x64_i8(a, b, c, 0, 0, 0);
+  }
+  static __device__ __forceinline__ bool fires(int32_t v, int32_t lo, int32_t) { return v >= lo; }
+};
+
+__device__ __forceinline__ int shfl_xor_i(int v, int mask) { return __shfl_xor(v, mask, 64); }
+
+// Output function for eight consecutive channels co0..co0+7 of one output pixel.
+// s0, s1: the eight sums (fp32 bit patterns or int32); dbyte: their decisions, bit k = channel co0+k;
+// o: element offset of channel co0 in y / residual.
+template <typename Tr>
+__device__ __forceinline__ void finish_store8(const Params& p, i32x4 s0, i32x4 s1, uint32_t dbyte, int co0,
+                                              long long o) {
+  if constexpr (Tr::kDtype == CG_I8) {
+    int32_t v[8];
+    int8_t res8[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    if (p.epilogue & CG_EPI_RESIDUAL) *(uint2*)res8 = *(const uint2*)((const int8_t*)p.residual + o);
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+      const int32_t s = k < 4 ? s0[k] : s1[k - 4];
+      const bool f = p.gated ? ((dbyte >> k) & 1u) : true;
+      const int co = co0 + k;
+      const long long r = (p.epilogue & CG_EPI_RESIDUAL) ? (long long)res8[k] * p.rq_res_mult : 0;
+      if (p.out_dtype == CG_I32) {
+        long long a = (long long)s + r;
+        if ((p.epilogue & CG_EPI_RELU) && a < 0) a = 0;
+        a = a > 2147483647ll ? 2147483647ll : a;
+        a = a < -2147483648ll ? -2147483648ll : a;
+        v[k] = (int32_t)a;
+      } else {
+        long long t = (long long)s * (f ? p.mult1[co] : p.mult0[co]);
+        t += (long long)p.bias[co] * (1ll << p.rq_shift);
+        t += r;
+        if (p.rq_shift > 0) t = (t + (1ll << (p.rq_shift - 1))) >> p.rq_shift;
+        const long long lo = (p.epilogue & CG_EPI_RELU) ? 0 : -128;
+        t = t < lo ? lo : t;
+        t = t > 127 ? 127 : t;
+        v[k] = (int32_t)t;
+      }
+    }
+    if (p.out_dtype == CG_I32) {
+      *(i32x4*)((int32_t*)p.y + o) = i32x4{v[0], v[1], v[2], v[3]};
+      *(i32x4*)((int32_t*)p.y + o + 4) = i32x4{v[4], v[5], v[6], v[7]};
+    } else {
+      int8_t b8[8];
+#pragma unroll
+      for (int k = 0; k < 8; ++k) b8[k] = (int8_t)v[k];
+      *(uint2*)((int8_t*)p.y + o) = *(const uint2*)b8;
+    }
+  } else {
+    float v[8];
+    float res[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    if (p.epilogue & CG_EPI_RESIDUAL) {
+      if (p.out_dtype == CG_F32) {
+        const f32x4 r0 = *(const f32x4*)((const float*)p.residual + o);
+        const f32x4 r1 = *(const f32x4*)((const float*)p.residual + o + 4);
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+          res[k] = r0[k];
+          res[k + 4] = r1[k];
+        }
+      } else {
+        uint16_t rb[8];
+        *(i32x4*)rb = *(const i32x4*)((const uint16_t*)p.residual + o);
+#pragma unroll
+        for (int k = 0; k < 8; ++k) res[k] = bf16_to_float(rb[k]);
+      }
+    }
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+      const float s = __int_as_float(k < 4 ? s0[k] : s1[k - 4]);
+      const bool f = p.gated ? ((dbyte >> k) & 1u) : true;
+      const int co = co0 + k;
+      float a = s;
+      if (p.epilogue & CG_EPI_AFFINE) a = f ? fmaf(p.sc1[co], s, p.sh1[co]) : fmaf(p.sc0[co], s, p.sh0[co]);
+      if (p.epilogue & CG_EPI_RESIDUAL) a += res[k];
+      if (p.epilogue & CG_EPI_RELU) a = fmaxf(a, 0.0f);
+      v[k] = a;
+    }
+    if (p.out_dtype == CG_F32) {
+      *(f32x4*)((float*)p.y + o) = f32x4{v[0], v[1], v[2], v[3]};
+      *(f32x4*)((float*)p.y + o + 4) = f32x4{v[4], v[5], v[6], v[7]};
+    } else {
+      uint16_t ob[8];
+#pragma unroll
+      for (int k = 0; k < 8; ++k) ob[k] = float_to_bf16(v[k]);
+      *(i32x4*)((uint16_t*)p.y + o) = *(const i32x4*)ob;
+    }
+  }
+}
+
+// weight prepack shared by both matrix-core kernels (defined in kernels_mfma.hip):
+// [c_out][taps][c] -> [column block][stage][e = 4*step + lane group][bn][16 bytes]
+hipError_t launch_pack_weights(const void* w, void* out, int c_out, int taps, int c_phase, int eb, int ch, int bn,
+                               int cbq, int stages, int tsteps, hipStream_t s);
+
+}  // namespace cg

@@ -15,8 +15,12 @@ def _say(rep):
     return rep
 
 
-def imagenet_small(n):
-    return W.imagenet_shapes(n=n)
+VARIANTS = [B.CG_VARIANT_MFMA, B.CG_VARIANT_MFMA_COMPACT]
+VNAMES = ["blockskip", "compact"]
+
+
+def _supported(shape, variant):
+    return not (variant == B.CG_VARIANT_MFMA_COMPACT and shape.k != 3)
 
 
 SMALL = [
@@ -40,60 +44,70 @@ SMALL = [
 ]
 
 
+@pytest.mark.parametrize("variant", VARIANTS, ids=VNAMES)
 @pytest.mark.parametrize("shape", SMALL, ids=[s.name for s in SMALL])
-def test_mfma_bf16_matches_oracle(shape):
+def test_mfma_bf16_matches_oracle(shape, variant):
+    if not _supported(shape, variant):
+        pytest.skip("1x1 layers run on the block-skipping kernel")
     inp = W.make_inputs(shape, 1000 + shape.c_out + shape.h, kind="coherent", rho=0.3, round_bf16=True)
     gate = W.calibrate_gate(inp, 0.30, sample_images=None)
-    rep = _say(P.run_float(inp, gate, in_dtype=B.CG_BF16, out_dtype=B.CG_F32, variant=B.CG_VARIANT_MFMA,
+    rep = _say(P.run_float(inp, gate, in_dtype=B.CG_BF16, out_dtype=B.CG_F32, variant=variant,
                            name=shape.name + " bf16"))
-    assert rep.variant == B.CG_VARIANT_MFMA
+    assert rep.variant == variant
     assert 0.1 < rep.fired_frac < 0.6
 
 
+@pytest.mark.parametrize("variant", VARIANTS, ids=VNAMES)
 @pytest.mark.parametrize("shape", SMALL, ids=[s.name for s in SMALL])
-def test_mfma_int8_bit_exact(shape):
+def test_mfma_int8_bit_exact(shape, variant):
+    if not _supported(shape, variant):
+        pytest.skip("1x1 layers run on the block-skipping kernel")
     if shape.c_base % 16:
         pytest.skip("int8 matrix-core path needs 16-channel groups")
     inp = W.make_inputs(shape, 2000 + shape.c_out + shape.h, kind="coherent", rho=0.35)
     q = W.quantize_int8(inp)
     thr = W.calibrate_gate_int8(q, 0.35, sample_images=None)
-    rep = _say(P.run_int8(q, thr, variant=B.CG_VARIANT_MFMA, name=shape.name + " int8"))
-    assert rep.variant == B.CG_VARIANT_MFMA
+    rep = _say(P.run_int8(q, thr, variant=variant, name=shape.name + " int8"))
+    assert rep.variant == variant
     assert 0.1 < rep.fired_frac < 0.6
 
 
+@pytest.mark.parametrize("variant", VARIANTS, ids=VNAMES)
 @pytest.mark.parametrize("kind", ["iid", "literal"])
-def test_mfma_bf16_unclustered_maps(kind):
+def test_mfma_bf16_unclustered_maps(kind, variant):
     shape = W.LayerShape("m_lit", 2, 28, 28, 128, 128)
     inp = W.make_inputs(shape, 31, kind=kind, rho=0.35, round_bf16=True)
     gate = W.calibrate_gate(inp, 0.35, sample_images=None)
-    _say(P.run_float(inp, gate, variant=B.CG_VARIANT_MFMA, name="unclustered " + kind))
+    _say(P.run_float(inp, gate, variant=variant, name="unclustered " + kind))
 
 
+@pytest.mark.parametrize("variant", VARIANTS, ids=VNAMES)
 @pytest.mark.parametrize("delta,frac", [(-np.inf, 1.0), (np.inf, 0.0)])
-def test_mfma_delta_infinite(delta, frac):
+def test_mfma_delta_infinite(delta, frac, variant):
     shape = W.LayerShape("m_inf", 2, 14, 14, 64, 64)
     inp = W.make_inputs(shape, 41, kind="iid", round_bf16=True)
     gate = W.calibrate_gate(inp, 0.3, sample_images=None)
     gate.delta[:] = delta
-    rep = _say(P.run_float(inp, gate, variant=B.CG_VARIANT_MFMA, name="delta=%s" % delta))
+    rep = _say(P.run_float(inp, gate, variant=variant, name="delta=%s" % delta))
     assert rep.fired_frac == frac and rep.flips == 0
     q = W.quantize_int8(W.make_inputs(shape, 42, kind="iid"))
     thr = np.full(64, np.iinfo(np.int32).min if delta < 0 else np.iinfo(np.int32).max, np.int32)
-    rep = _say(P.run_int8(q, thr, variant=B.CG_VARIANT_MFMA, name="int8 delta=%s" % delta))
+    rep = _say(P.run_int8(q, thr, variant=variant, name="int8 delta=%s" % delta))
     assert rep.fired_frac == frac
 
 
-def test_mfma_dense_comparator():
+@pytest.mark.parametrize("variant", VARIANTS, ids=VNAMES)
+def test_mfma_dense_comparator(variant):
     shape = W.LayerShape("m_dense", 2, 28, 28, 64, 128, groups=1)
     inp = W.make_inputs(shape, 51, kind="iid", round_bf16=True)
-    rep = _say(P.run_float(inp, None, variant=B.CG_VARIANT_MFMA, name="dense bf16"))
+    rep = _say(P.run_float(inp, None, variant=variant, name="dense bf16"))
     assert rep.fired_frac == 0.0
     q = W.quantize_int8(W.make_inputs(shape, 52, kind="iid"))
-    _say(P.run_int8(q, None, variant=B.CG_VARIANT_MFMA, name="dense int8"))
+    _say(P.run_int8(q, None, variant=variant, name="dense int8"))
 
 
-def test_mfma_epilogues_bf16():
+@pytest.mark.parametrize("variant", VARIANTS, ids=VNAMES)
+def test_mfma_epilogues_bf16(variant):
     shape = W.LayerShape("m_epi", 3, 14, 14, 128, 128)
     inp = W.make_inputs(shape, 61, kind="coherent", rho=0.3, round_bf16=True)
     gate = W.calibrate_gate(inp, 0.3, sample_images=None)
@@ -102,24 +116,25 @@ def test_mfma_epilogues_bf16():
                scale1=rng.uniform(0.5, 1.5, 128), shift1=rng.normal(0, 0.1, 128))
     res = rng.standard_normal((3, 14, 14, 128)).astype(np.float32)
     for out_dtype in (B.CG_F32, B.CG_BF16):
-        _say(P.run_float(inp, gate, out_dtype=out_dtype, variant=B.CG_VARIANT_MFMA, affine=aff, residual=res,
+        _say(P.run_float(inp, gate, out_dtype=out_dtype, variant=variant, affine=aff, residual=res,
                          epilogue=B.CG_EPI_RELU | B.CG_EPI_AFFINE | B.CG_EPI_RESIDUAL,
                          name="epilogue out=%d" % out_dtype))
-    _say(P.run_float(inp, gate, out_dtype=B.CG_BF16, variant=B.CG_VARIANT_MFMA, epilogue=0, name="no epilogue bf16 out"))
-    _say(P.run_float(inp, gate, variant=B.CG_VARIANT_MFMA, delta_hi=gate.delta + 0.8, name="two-sided mfma"))
+    _say(P.run_float(inp, gate, out_dtype=B.CG_BF16, variant=variant, epilogue=0, name="no epilogue bf16 out"))
+    _say(P.run_float(inp, gate, variant=variant, delta_hi=gate.delta + 0.8, name="two-sided mfma"))
 
 
-def test_mfma_epilogues_int8():
+@pytest.mark.parametrize("variant", VARIANTS, ids=VNAMES)
+def test_mfma_epilogues_int8(variant):
     shape = W.LayerShape("m_epi8", 3, 14, 14, 128, 128)
     q = W.quantize_int8(W.make_inputs(shape, 71, kind="coherent", rho=0.35))
     thr = W.calibrate_gate_int8(q, 0.35, sample_images=None)
     rng = np.random.default_rng(71)
     rq = W.requant_params(q, rng)
     res = rng.integers(-128, 128, (3, 14, 14, 128)).astype(np.int8)
-    _say(P.run_int8(q, thr, out_i8=True, rq=rq, residual=res, rq_res_mult=1 << 14, variant=B.CG_VARIANT_MFMA,
+    _say(P.run_int8(q, thr, out_i8=True, rq=rq, residual=res, rq_res_mult=1 << 14, variant=variant,
                     epilogue=B.CG_EPI_RESIDUAL | B.CG_EPI_RELU, name="int8 requant+res+relu"))
-    _say(P.run_int8(q, thr, out_i8=True, rq=rq, variant=B.CG_VARIANT_MFMA, epilogue=0, name="int8 requant"))
-    _say(P.run_int8(q, thr, residual=res, rq_res_mult=5, variant=B.CG_VARIANT_MFMA, epilogue=B.CG_EPI_RESIDUAL,
+    _say(P.run_int8(q, thr, out_i8=True, rq=rq, variant=variant, epilogue=0, name="int8 requant"))
+    _say(P.run_int8(q, thr, residual=res, rq_res_mult=5, variant=variant, epilogue=B.CG_EPI_RESIDUAL,
                     name="int32 + residual"))
 
 
@@ -130,7 +145,7 @@ def test_mfma_matches_naive_kernel_decisions():
     q = W.quantize_int8(W.make_inputs(shape, 81, kind="coherent", rho=0.35))
     thr = W.calibrate_gate_int8(q, 0.35, sample_images=None)
     outs = []
-    for variant in (B.CG_VARIANT_NAIVE, B.CG_VARIANT_MFMA):
+    for variant in (B.CG_VARIANT_NAIVE, B.CG_VARIANT_MFMA, B.CG_VARIANT_MFMA_COMPACT):
         x = torch.from_numpy(q.x).cuda()
         layer = B.GatedConv(n_max=2, h=28, w=28, c_in=128, c_out=128, c_base=32,
                             w_base=torch.from_numpy(q.w_base).cuda(), w_cond=torch.from_numpy(q.w_cond).cuda(),
@@ -142,5 +157,6 @@ def test_mfma_matches_naive_kernel_decisions():
             assert torch.equal(u, v)
         outs.append([t.cpu() for t in b])
         layer.close()
-    for u, v in zip(*outs):
-        assert torch.equal(u, v)
+    for other in outs[1:]:
+        for u, v in zip(outs[0], other):
+            assert torch.equal(u, v)
