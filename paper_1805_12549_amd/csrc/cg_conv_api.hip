@@ -361,7 +361,14 @@ int cg_conv_forward(cg_conv* h, int32_t n, const void* x, const void* residual, 
   p.rq_shift = d.rq_shift;
   p.rq_res_mult = d.rq_res_mult;
   p.words = (d.c_out + 31) / 32;
-  { const char* dbg = getenv("CG_DEBUG_SKIP"); p.debug = dbg ? atoi(dbg) : 0; }
+#ifdef CG_PROFILE_KNOBS
+  {  // developer builds only: switches off parts of the kernel to time the rest (results are then wrong)
+    const char* dbg = getenv("CG_DEBUG_SKIP");
+    p.debug = dbg ? atoi(dbg) : 0;
+  }
+#else
+  p.debug = 0;
+#endif
   const size_t ts = l.table_stride;
   p.thr_f = (const float*)(pk + 0 * ts);
   p.thr_hi_f = (const float*)(pk + 1 * ts);

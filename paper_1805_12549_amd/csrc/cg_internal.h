@@ -82,8 +82,8 @@ MfmaPlan mfma_plan(const cg_conv_desc& d);
 struct Mfma2Plan {
   int ok;
   int elem_bytes, ch;      // bytes per element; channels per 16-byte chunk
-  int ngw;                 // 16-pixel row groups per wavefront in the base phase (2 or 4)
-  int bm;                  // ngw*64: pixels per tile, padded
+  int ngw;                 // 16-pixel row groups per wavefront in the base phase (1 or 2)
+  int bm;                  // ngw*16*wavefronts: pixels per tile, padded
   int n_cb;                // c_out / 64
   int tr;                  // global output rows per tile
   int hp;                  // h + 2*pad
@@ -95,7 +95,9 @@ struct Mfma2Plan {
   int cbq;                 // 16-byte channel chunks per pixel per K stage: 1, 2 or 4
   int stages[2];           // K stages of the base / conditional phase
   int tsteps;              // MFMA K steps per stage = ceil(9*cbq/4)
-  int kp;                  // patch chunks per thread per stage = ceil(npix*cbq/256)
+  int kp;                  // patch chunk slots per thread per stage
+  int pln, nps;            // bytes / 16-byte slots per chunk plane of the LDS patch (npix pixels + a zero pixel, padded)
+  unsigned magic_nps;
   int patch_bytes, w_bytes, stage_bytes;
   int lds_goff, lds_outpp, lds_outm, lds_flag, lds_clist, lds_rank, lds_dbits, lds_colcnt, lds_zero, lds_misc,
       lds_stage, lds_total;

@@ -19,9 +19,11 @@
 //
 // K is consumed in stages of CBQ 16-byte channel chunks per pixel.  Stage s+1 is fetched with
 // LDS-direct loads (global_load_lds_dwordx4) into the second buffer while stage s is multiplied.
-// The patch is stored as [pixel][CBQ chunks + 1 spare chunk]: the odd pixel stride keeps the
-// 16 lanes of an operand read on distinct banks and makes operand addresses additive
-// (pixel base + tap offset), the spare chunk holds zeros for the K padding.
+// The patch is stored as CBQ planes [chunk][pixel], 16 bytes per pixel: the 16 lanes of one lane
+// group of an operand read (16 consecutive pixels, one chunk) then cover 256 contiguous bytes and
+// the four lane groups sit a multiple of 256 bytes apart, the pattern the LDS serves at full
+// rate; operand addresses are additive (pixel + chunk plane + tap offset).  Each plane ends
+// in a zero pixel that the K padding reads.
 #include <cstdlib>
 
 #include "cg_mfma_common.h"
@@ -30,9 +32,11 @@ namespace cg {
 
 namespace {
 
-constexpr int kThreads = 256;
+constexpr int kWaves = 8;              // wavefronts per workgroup: two per SIMD, so that one wavefront's
+                                       // LDS / global issue overlaps the other's MFMAs
+constexpr int kThreads = kWaves * 64;
 constexpr int kBN = 64;
-constexpr int kKP = 14;   // patch chunk slots per thread per stage, at most
+constexpr int kKP = 8;    // patch chunk slots per thread per stage, at most
 // Static LDS: two stage buffers and one table area, three separate objects so that the compiler's
 // alias analysis keeps LDS-direct loads into one buffer from stalling reads of the other.
 constexpr int kStageBytes = 72 * 1024;
@@ -50,23 +54,29 @@ __device__ __forceinline__ void lds_direct_16(const char* gsrc, char* ldst) {
 template <int CBQ>
 struct StageGeom {
   static constexpr int T = (9 * CBQ + 3) / 4;                  // MFMA K steps per stage
-  static constexpr int SL = CBQ == 1 ? 1 : CBQ + 1;            // 16-byte slots per patch pixel
-  static constexpr int PS = SL * 16;                           // bytes per patch pixel
 };
 
 // One K stage of MFMAs for this wavefront: NRL pixel groups x four 16-channel fragments.
 // K step t multiplies chunk e = 4t + lg of the stage (tap e / CBQ, channel chunk e % CBQ);
-// arow[fr] is the lane's patch offset of group fr (pixel base + chunk), aoff[t] the tap offset.
-// Step t: wait for its operands, start the LDS reads of step t+1 and a slice of the next
-// stage's global->LDS loads (issue(t)), then issue the MFMAs of step t over them.
+// arow[fr] is the lane's patch offset of group fr (pixel + chunk plane), aoff[t] the tap offset
+// (negative for the K padding past the ninth tap, which reads the zero pixel at zaddr).
+// A wavefront issues in order, so the LDS reads of step t+1 (and a slice of the next stage's
+// global->LDS loads, issue(t)) are interleaved one by one between the MFMAs of step t; the
+// scheduling barriers pin that order.
 template <typename Tr, int CBQ, int NRL, int NRMAX, typename IssueFn>
 __device__ __forceinline__ void mma_stage(const char* __restrict__ patch, const char* __restrict__ wb,
-                                          const int (&arow)[NRMAX], const int (&aoff)[StageGeom<CBQ>::T],
+                                          const int (&arow)[NRMAX], const int (&aoff)[StageGeom<CBQ>::T], int zaddr,
                                           typename Tr::acc4 (&acc)[NRMAX][4], IssueFn&& issue) {
   constexpr int T = StageGeom<CBQ>::T;
+  auto a_addr = [&](int fr, int t) __attribute__((always_inline)) {
+    if constexpr (CBQ == 4) return arow[fr] + aoff[t];
+    return aoff[t] >= 0 ? arow[fr] + aoff[t] : zaddr;
+  };
+  constexpr int R = NRL + 4;      // operand reads per K step
+  constexpr int M = NRL * 4;      // MFMAs per K step
   i32x4 a[2][NRL], b[2][4];
 #pragma unroll
-  for (int fr = 0; fr < NRL; ++fr) a[0][fr] = *(const i32x4*)(patch + arow[fr] + aoff[0]);
+  for (int fr = 0; fr < NRL; ++fr) a[0][fr] = *(const i32x4*)(patch + a_addr(fr, 0));
 #pragma unroll
   for (int fc = 0; fc < 4; ++fc) b[0][fc] = *(const i32x4*)(wb + fc * 256);
 #pragma unroll
@@ -74,32 +84,31 @@ __device__ __forceinline__ void mma_stage(const char* __restrict__ patch, const 
     const int cur = t & 1, nxt = cur ^ 1;
     __builtin_amdgcn_s_waitcnt(0xC07F);   // lgkmcnt(0): operands of step t are in registers
     __builtin_amdgcn_sched_barrier(0);
-    if (t + 1 < T) {
 #pragma unroll
-      for (int fr = 0; fr < NRL; ++fr) a[nxt][fr] = *(const i32x4*)(patch + arow[fr] + aoff[t + 1]);
+    for (int i = 0; i < R; ++i) {
+      if (t + 1 < T) {
+        if (i < NRL)
+          a[nxt][i] = *(const i32x4*)(patch + a_addr(i, t + 1));
+        else
+          b[nxt][i - NRL] = *(const i32x4*)(wb + (t + 1) * (4 * kBN * 16) + (i - NRL) * 256);
+      }
+      if (i == 1) issue(t);
 #pragma unroll
-      for (int fc = 0; fc < 4; ++fc) b[nxt][fc] = *(const i32x4*)(wb + (t + 1) * (4 * kBN * 16) + fc * 256);
+      for (int j = (i * M) / R; j < ((i + 1) * M) / R; ++j)
+        acc[j >> 2][j & 3] = Tr::mfma(a[cur][j >> 2], b[cur][j & 3], acc[j >> 2][j & 3]);
+      __builtin_amdgcn_sched_barrier(0);
     }
-    issue(t);
-    __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-    for (int fr = 0; fr < NRL; ++fr)
-#pragma unroll
-      for (int fc = 0; fc < 4; ++fc) acc[fr][fc] = Tr::mfma(a[cur][fr], b[cur][fc], acc[fr][fc]);
-    __builtin_amdgcn_sched_barrier(0);
   }
 }
 
 // dispatch on the (workgroup-uniform) number of pixel groups per wavefront
 template <typename Tr, int CBQ, int NRMAX, typename IssueFn>
 __device__ __forceinline__ void mma_dispatch(int nr, const char* patch, const char* wb, const int (&arow)[NRMAX],
-                                             const int (&aoff)[StageGeom<CBQ>::T],
+                                             const int (&aoff)[StageGeom<CBQ>::T], int zaddr,
                                              typename Tr::acc4 (&acc)[NRMAX][4], IssueFn&& issue) {
   switch (nr) {
-    case 1: mma_stage<Tr, CBQ, 1, NRMAX>(patch, wb, arow, aoff, acc, issue); break;
-    case 2: mma_stage<Tr, CBQ, 2, NRMAX>(patch, wb, arow, aoff, acc, issue); break;
-    case 3: if constexpr (NRMAX >= 3) mma_stage<Tr, CBQ, 3, NRMAX>(patch, wb, arow, aoff, acc, issue); break;
-    case 4: if constexpr (NRMAX >= 4) mma_stage<Tr, CBQ, 4, NRMAX>(patch, wb, arow, aoff, acc, issue); break;
+    case 1: mma_stage<Tr, CBQ, 1, NRMAX>(patch, wb, arow, aoff, zaddr, acc, issue); break;
+    case 2: if constexpr (NRMAX >= 2) mma_stage<Tr, CBQ, 2, NRMAX>(patch, wb, arow, aoff, zaddr, acc, issue); break;
     default:
 #pragma unroll
       for (int t = 0; t < StageGeom<CBQ>::T; ++t) issue(t);
@@ -114,8 +123,9 @@ __global__ __launch_bounds__(kThreads, 1) void gated_conv_compact_kernel(Params 
   using acc4 = typename Tr::acc4;
   using acc_t = typename Tr::acc_t;
   using SG = StageGeom<CBQ>;
-  constexpr int BM = NGW * 64;
-  constexpr int T = SG::T, SL = SG::SL, PS = SG::PS;
+  constexpr int BM = NGW * 16 * kWaves;
+  constexpr int WROWS = (StageGeom<CBQ>::T * 256 + kThreads - 1) / kThreads;   // wave-wide rows of a weight stage slab
+  constexpr int T = SG::T;
   constexpr int LOGC = CBQ == 4 ? 2 : CBQ == 2 ? 1 : 0;
 
   __shared__ __align__(16) char bufA[kStageBytes];
@@ -157,7 +167,7 @@ __global__ __launch_bounds__(kThreads, 1) void gated_conv_compact_kernel(Params 
   const int base0 = img0 * g.hp + (R0 - img0 * p.ho) * p.stride;   // stacked padded input row of patch row 0
 
   // ---- per-tile tables: patch rows over wavefronts, patch columns over lanes ---------------------
-  for (int prow = wave; prow < g.pr_max; prow += 4) {
+  for (int prow = wave; prow < g.pr_max; prow += kWaves) {
     const int srow = base0 + prow;
     const int img = fdiv(srow, g.magic_hp);
     const int hi = srow - img * g.hp - p.pad;
@@ -191,29 +201,31 @@ __global__ __launch_bounds__(kThreads, 1) void gated_conv_compact_kernel(Params 
   __syncthreads();
   CG_STAMP();
 
-  // ---- this thread's load slots: slot ci = k*256 + tid of the patch is (pixel ci / SL, chunk ci % SL)
+  // ---- this thread's load slots: slot ci = k*threads + tid of the patch is (chunk plane ci / nps,
+  // pixel ci % nps); nps slots per plane, the ones past npix stay zero
   const char* xbytes = (const char*)p.x;
   const int eb = g.elem_bytes;
   int gsl[kKP];
   {
-    int gi[kKP];
-    const int last_slot = g.npix * SL - 1;
+    int gi[kKP], qq[kKP];
+    const int last_slot = CBQ * g.nps - 1;
 #pragma unroll
     for (int k = 0; k < kKP; ++k) {       // all table reads first, so that their latencies overlap
       int ci = k * kThreads + tid;
       ci = ci > last_slot ? last_slot : ci;
-      gi[k] = pix_goff[ci / SL];
+      qq[k] = fdiv(ci, g.magic_nps);
+      const int pix = ci - qq[k] * g.nps;
+      gi[k] = pix < g.npix ? pix_goff[pix] : -1;
     }
 #pragma unroll
     for (int k = 0; k < kKP; ++k) {
       gsl[k] = -1;
       const int ci = k * kThreads + tid;
       if (k < g.kp && ci <= last_slot) {
-        const int slot = ci - (ci / SL) * SL;
-        if (gi[k] >= 0 && slot < CBQ) {
-          gsl[k] = (int)(((long long)gi[k] * p.x_pixel_stride + slot * g.ch) * eb);
+        if (gi[k] >= 0) {
+          gsl[k] = (gi[k] * (int)p.x_pixel_stride + qq[k] * g.ch) * eb;   // the plan keeps x below 2 GiB
         } else {
-          // outside the image, or the spare chunk: zero once, never written again
+          // outside the image, or plane padding (the zero pixel): zero once, never written again
           *(i32x4*)(bufA + ci * 16) = i32x4{0, 0, 0, 0};
           *(i32x4*)(bufB + ci * 16) = i32x4{0, 0, 0, 0};
         }
@@ -230,11 +242,14 @@ __global__ __launch_bounds__(kThreads, 1) void gated_conv_compact_kernel(Params 
     const int ss = ph ? s - S0 : s;
     char* wdst = pdst + g.patch_bytes;
     const char* ws = (ph ? wpk1 : wpk0) + ((size_t)cbk * g.stages[ph] + ss) * g.wpk_stage_bytes;
-    lds_direct_16(ws + (t * kThreads + tid) * 16, wdst + (t * kThreads + wave * 64) * 16);
+    if (t < WROWS && !(p.debug & 64)) {
+      if (t * kThreads + tid < T * 256)
+        lds_direct_16(ws + (t * kThreads + tid) * 16, wdst + (t * kThreads + wave * 64) * 16);
+    }
     const char* xs = xbytes + (long long)((ph ? p.c_base : 0) + ss * CBQ * g.ch) * eb;
 #pragma unroll
     for (int k = 0; k < kKP; ++k) {
-      if (k % T == t && k < g.kp) {
+      if (k % T == t && k < g.kp && !(p.debug & 32)) {
         if (gsl[k] >= 0) lds_direct_16(xs + gsl[k], pdst + (k * kThreads + wave * 64) * 16);
       }
     }
@@ -245,8 +260,10 @@ __global__ __launch_bounds__(kThreads, 1) void gated_conv_compact_kernel(Params 
     char* wdst = pdst + g.patch_bytes;
     const char* ws = (ph ? wpk1 : wpk0) + ((size_t)cbk * g.stages[ph] + ss) * g.wpk_stage_bytes;
 #pragma unroll
-    for (int t = 0; t < T; ++t)
-      lds_direct_16(ws + (t * kThreads + tid) * 16, wdst + (t * kThreads + wave * 64) * 16);
+    for (int t = 0; t < WROWS; ++t) {
+      if (t * kThreads + tid < T * 256)
+        lds_direct_16(ws + (t * kThreads + tid) * 16, wdst + (t * kThreads + wave * 64) * 16);
+    }
     const char* xs = xbytes + (long long)((ph ? p.c_base : 0) + ss * CBQ * g.ch) * eb;
 #pragma unroll
     for (int k = 0; k < kKP; ++k) {
@@ -257,13 +274,14 @@ __global__ __launch_bounds__(kThreads, 1) void gated_conv_compact_kernel(Params 
   };
 
   // ---- per-lane K-step geometry: chunk e = 4t + lg is (tap, q) = (e / CBQ, e % CBQ) -----------------
-  // byte offset of that chunk relative to (pixel base + q*16); the K padding reads the spare chunk
+  // byte offset of the tap inside plane q; the K padding reads the plane's zero pixel
   const int q = lg & (CBQ - 1);
+  const int zaddr = q * g.pln + g.npix * 16;
   int aoff[T];
 #pragma unroll
   for (int t = 0; t < T; ++t) {
     const int tap = (4 * t + lg) >> LOGC;
-    aoff[t] = tap < 9 ? ((tap / 3) * g.pw + (tap % 3)) * PS : (CBQ - q) * 16;
+    aoff[t] = tap < 9 ? ((tap / 3) * g.pw + (tap % 3)) * 16 : -1;
   }
 
   // ---- base-path rows of this wavefront --------------------------------------------------------------
@@ -272,8 +290,8 @@ __global__ __launch_bounds__(kThreads, 1) void gated_conv_compact_kernel(Params 
   int arow[NGW], arow_c[NGW];
 #pragma unroll
   for (int fr = 0; fr < NGW; ++fr) {
-    arow[fr] = out_pp[(wave * NGW + fr) * 16 + lj] * PS + q * 16;
-    arow_c[fr] = q * 16;
+    arow[fr] = out_pp[(wave * NGW + fr) * 16 + lj] * 16 + q * g.pln;
+    arow_c[fr] = q * g.pln;
   }
 
   acc4 accP[NGW][4], accR[NGW][4];
@@ -285,10 +303,24 @@ __global__ __launch_bounds__(kThreads, 1) void gated_conv_compact_kernel(Params 
       accR[fr][fc] = acc4{0, 0, 0, 0};
     }
 
-  unsigned long long dmask = 0;   // per-lane decisions, bit (fr*4+fc)*4+i
   int nrc = 0;                    // live compacted groups of this wavefront
   int nr_wg = 0;                  // compacted groups every wavefront multiplies = ceil(groups / 4)
   const int wlane = (lg * kBN + lj) * 16;   // lane's offset inside a weight K-step slab
+
+  // gate thresholds of this lane's four channels, fetched before any prefetch is in flight
+  // (a later global load would queue behind the stage loads)
+  acc_t tlo[4], thi[4];
+#pragma unroll
+  for (int fc = 0; fc < 4; ++fc) {
+    const int co = cbk * kBN + fc * 16 + lj;
+    if constexpr (Tr::kDtype == CG_I8) {
+      tlo[fc] = p.gated ? p.thr_i[co] : 0;
+      thi[fc] = 0;
+    } else {
+      tlo[fc] = p.gated ? p.thr_f[co] : 0.0f;
+      thi[fc] = p.gated ? p.thr_hi_f[co] : 0.0f;
+    }
+  }
 
   CG_STAMP();
   issue_stage(0, bufA);
@@ -310,85 +342,87 @@ __global__ __launch_bounds__(kThreads, 1) void gated_conv_compact_kernel(Params 
       for (int t = 0; t < T; ++t) part(t);
     } else if (s < S0) {
       // every wavefront multiplies NGW groups: the ones past the tile's end read pixel 0 and are dropped
-      mma_stage<Tr, CBQ, NGW, NGW>(patch, wb, arow, aoff, accP, part);
+      mma_stage<Tr, CBQ, NGW, NGW>(patch, wb, arow, aoff, zaddr, accP, part);
     } else {
-      mma_dispatch<Tr, CBQ, NGW>(nr_wg, patch, wb, arow_c, aoff, accR, part);
+      mma_dispatch<Tr, CBQ, NGW>(nr_wg, patch, wb, arow_c, aoff, zaddr, accR, part);
     }
     if (s == 1) CG_STAMP();
 
     if (s == S0 - 1 && p.gated) {
+      CG_STAMP();
       // ---- gate ------------------------------------------------------------------------------
-      acc_t tlo[4], thi[4];
-#pragma unroll
-      for (int fc = 0; fc < 4; ++fc) {
-        const int co = cbk * kBN + fc * 16 + lj;
-        if constexpr (Tr::kDtype == CG_I8) {
-          tlo[fc] = p.thr_i[co];
-          thi[fc] = 0;
-        } else {
-          tlo[fc] = p.thr_f[co];
-          thi[fc] = p.thr_hi_f[co];
-        }
-      }
+      // images (relative to img0) of this wavefront's first and last live pixel
+      int last_row = (wave * NGW + ngrp) * 16 - 1;
+      if (last_row >= g.bm_valid) last_row = g.bm_valid - 1;
+      const int il0 = fdiv(R0 + fdiv(wave * NGW * 16, g.magic_wo), g.magic_ho) - img0;
+      const int il1 = ngrp > 0 ? fdiv(R0 + fdiv(last_row, g.magic_wo), g.magic_ho) - img0 : il0;
+      int cnt[4] = {0, 0, 0, 0};   // fired gates of this lane per channel fragment
+      unsigned dm = 0;             // this lane's decisions, bit fr*16 + fc*4 + i
+      const int li = lane & 3, lgg = (lane >> 2) & 3;   // lanes 0..15 assemble the decision words of row `lane`
 #pragma unroll
       for (int fr = 0; fr < NGW; ++fr) {
         if (fr >= ngrp) continue;
         const int row_base = (wave * NGW + fr) * 16;
-        bool rv[4], anyf[4];
+        unsigned vm = 0;           // bit i: pixel 4*lg+i is a real output pixel
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          rv[i] = out_m[row_base + 4 * lg + i] >= 0;
-          anyf[i] = false;
-        }
-        int last_row = row_base + 15;
-        if (last_row >= g.bm_valid) last_row = g.bm_valid - 1;
-        const int il_first = fdiv(R0 + fdiv(row_base, g.magic_wo), g.magic_ho) - img0;
-        const int il_last = fdiv(R0 + fdiv(last_row, g.magic_wo), g.magic_ho) - img0;
-        unsigned long long prev_sel = 0;
+        for (int i = 0; i < 4; ++i) vm |= (out_m[row_base + 4 * lg + i] >= 0 ? 1u : 0u) << i;
+        const unsigned long long vball[4] = {__ballot(vm & 1u), __ballot(vm & 2u), __ballot(vm & 4u), __ballot(vm & 8u)};
+        unsigned d16 = 0;          // this lane's 16 decisions of the group, bit fc*4 + i
+        unsigned prev_sel = 0;
 #pragma unroll
         for (int fc = 0; fc < 4; ++fc) {
           unsigned long long mk[4];
-          int c = 0;
 #pragma unroll
           for (int i = 0; i < 4; ++i) {
-            const bool f = rv[i] && Tr::fires(accP[fr][fc][i], tlo[fc], thi[fc]);
-            mk[i] = __ballot(f);
-            if (f) {
-              dmask |= 1ull << ((fr * 4 + fc) * 4 + i);
-              anyf[i] = true;
-              ++c;
-            }
+            const bool f = Tr::fires(accP[fr][fc][i], tlo[fc], thi[fc]);
+            mk[i] = __ballot(f) & vball[i];
+            d16 |= (f ? 1u : 0u) << (fc * 4 + i);
           }
-          if (il_first == il_last) {
-            c += shfl_xor_i(c, 16);
-            c += shfl_xor_i(c, 32);
-            if (lane < 16 && c) atomicAdd(&colcnt[il_first * kBN + fc * 16 + lj], (uint32_t)c);
-          } else {
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-              if ((dmask >> ((fr * 4 + fc) * 4 + i)) & 1ull) {
-                const int il = fdiv(R0 + fdiv(row_base + 4 * lg + i, g.magic_wo), g.magic_ho) - img0;
-                atomicAdd(&colcnt[il * kBN + fc * 16 + lj], 1u);
-              }
-            }
-          }
-          // decision words: lane l < 16 assembles the 16 bits of row l from the four ballots
-          const int li = lane & 3, lgg = (lane >> 2) & 3;
-          unsigned long long sel = li == 0 ? mk[0] : li == 1 ? mk[1] : li == 2 ? mk[2] : mk[3];
-          sel = (sel >> (16 * lgg)) & 0xffffull;
+          // bits 16*g .. 16*g+15 of ballot i are the 16 channels of pixel 4*g+i
+          const unsigned long long m64 = li == 0 ? mk[0] : li == 1 ? mk[1] : li == 2 ? mk[2] : mk[3];
+          const unsigned half = lgg < 2 ? (unsigned)m64 : (unsigned)(m64 >> 32);
+          const unsigned sel = (half >> (16 * (lgg & 1))) & 0xffffu;
           if (fc & 1) {
-            if (lane < 16) dbits[(row_base + lane) * 2 + (fc >> 1)] = (uint32_t)(prev_sel | (sel << 16));
+            if (lane < 16) dbits[(row_base + lane) * 2 + (fc >> 1)] = prev_sel | (sel << 16);
           } else {
             prev_sel = sel;
           }
         }
+        d16 &= vm * 0x1111u;       // drop the rows past the end of the tile
+        dm |= d16 << (fr * 16);
+        const unsigned anyb = (d16 | (d16 >> 4) | (d16 >> 8) | (d16 >> 12)) & 0xfu;
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-          const unsigned long long b = __ballot(anyf[i]);
-          if (lj == 0) flag[row_base + 4 * lg + i] = ((b >> (16 * lg)) & 0xffffull) != 0ull;
+          const unsigned long long b = __ballot((anyb >> i) & 1u);
+          const unsigned half = lg < 2 ? (unsigned)b : (unsigned)(b >> 32);
+          if (lj == 0) flag[row_base + 4 * lg + i] = ((half >> (16 * (lg & 1))) & 0xffffu) != 0u;
         }
       }
+#pragma unroll
+      for (int fc = 0; fc < 4; ++fc) {
+        unsigned msk = 0;
+#pragma unroll
+        for (int fr = 0; fr < NGW; ++fr) msk |= 0xfu << (fr * 16 + fc * 4);
+        cnt[fc] = __popc(dm & msk);
+      }
+      // per-(image, channel) counts: one LDS atomic per fragment when the wavefront sits in one image
+      if (il0 == il1) {
+#pragma unroll
+        for (int fc = 0; fc < 4; ++fc)
+          if (cnt[fc]) atomicAdd(&colcnt[il0 * kBN + fc * 16 + lj], (uint32_t)cnt[fc]);
+      } else {
+#pragma nounroll
+        for (int e = 0; e < NGW * 16; ++e) {
+          if ((dm >> e) & 1u) {
+            const int row = (wave * NGW + (e >> 4)) * 16 + 4 * lg + (e & 3);
+            const int il = fdiv(R0 + fdiv(row, g.magic_wo), g.magic_ho) - img0;
+            atomicAdd(&colcnt[il * kBN + ((e >> 2) & 3) * 16 + lj], 1u);
+          }
+        }
+      }
+      CG_STAMP();
       __syncthreads();
+      CG_STAMP();
 
       // ---- compaction: every wavefront scans all flags, thread r places row r ----------------------
       int n_act = 0, my_prefix = 0;
@@ -409,16 +443,17 @@ __global__ __launch_bounds__(kThreads, 1) void gated_conv_compact_kernel(Params 
       }
       __syncthreads();
 
-      // compacted group c (16 rows) goes to wavefront c % 4
+      // compacted group c (16 rows) goes to wavefront c % kWaves
       const int ngc = (n_act + 15) >> 4;
-      nrc = ngc > wave ? (ngc - wave + 3) >> 2 : 0;
-      nr_wg = (ngc + 3) >> 2;
+      nrc = ngc > wave ? (ngc - wave + kWaves - 1) / kWaves : 0;
+      nr_wg = (ngc + kWaves - 1) / kWaves;
 #pragma unroll
       for (int fr = 0; fr < NGW; ++fr) {
-        const int c = (wave + 4 * fr) * 16 + lj;
-        arow_c[fr] = out_pp[c < n_act ? clist[c] : 0] * PS + q * 16;
+        const int c = (wave + kWaves * fr) * 16 + lj;
+        arow_c[fr] = out_pp[c < n_act ? clist[c] : 0] * 16 + q * g.pln;
       }
       if (n_act == 0) S = s + 1;   // nothing fired in this tile: the conditional stages are skipped
+      CG_STAMP();
     }
 
     __builtin_amdgcn_s_waitcnt(0x0F70);
@@ -454,7 +489,7 @@ __global__ __launch_bounds__(kThreads, 1) void gated_conv_compact_kernel(Params 
       for (int fc = 0; fc < 4; ++fc)
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-          const int crow = (wave + 4 * fr) * 16 + 4 * lg + i;
+          const int crow = (wave + kWaves * fr) * 16 + 4 * lg + i;
           tileR[crow * kBN + ((fc * 16 + lj) ^ (lg << 4))] = accR[fr][fc][i];
         }
     }
@@ -481,15 +516,16 @@ __global__ __launch_bounds__(kThreads, 1) void gated_conv_compact_kernel(Params 
       const i32x4 r1 = *(const i32x4*)(rp + 4);
 #pragma unroll
       for (int k = 0; k < 8; ++k) {
-        if ((db >> k) & 1u) {
-          if constexpr (Tr::kDtype == CG_I8) {
-            if (k < 4) s0[k] += r0[k]; else s1[k - 4] += r1[k - 4];
-          } else {
-            if (k < 4)
-              s0[k] = __float_as_int(__int_as_float(s0[k]) + __int_as_float(r0[k]));
-            else
-              s1[k - 4] = __float_as_int(__int_as_float(s1[k - 4]) + __int_as_float(r1[k - 4]));
-          }
+        const bool on = (db >> k) & 1u;
+        if constexpr (Tr::kDtype == CG_I8) {
+          const int r = on ? (k < 4 ? r0[k] : r1[k - 4]) : 0;
+          if (k < 4) s0[k] += r; else s1[k - 4] += r;
+        } else {
+          const float r = on ? __int_as_float(k < 4 ? r0[k] : r1[k - 4]) : 0.0f;
+          if (k < 4)
+            s0[k] = __float_as_int(__int_as_float(s0[k]) + r);
+          else
+            s1[k - 4] = __float_as_int(__int_as_float(s1[k - 4]) + r);
         }
       }
     }
@@ -536,14 +572,14 @@ hipError_t launch_one(const Mfma2Plan& g, const Params& p, const void* w0, const
 
 template <typename Tr>
 hipError_t launch_dtype(const Mfma2Plan& g, const Params& p, const void* w0, const void* w1, hipStream_t s) {
-  if (g.ngw == 4) {
-    if (g.cbq == 4) return launch_one<Tr, 4, 4>(g, p, w0, w1, s);
-    if (g.cbq == 2) return launch_one<Tr, 4, 2>(g, p, w0, w1, s);
-    return launch_one<Tr, 4, 1>(g, p, w0, w1, s);
+  if (g.ngw == 2) {
+    if (g.cbq == 4) return launch_one<Tr, 2, 4>(g, p, w0, w1, s);
+    if (g.cbq == 2) return launch_one<Tr, 2, 2>(g, p, w0, w1, s);
+    return launch_one<Tr, 2, 1>(g, p, w0, w1, s);
   }
-  if (g.cbq == 4) return launch_one<Tr, 2, 4>(g, p, w0, w1, s);
-  if (g.cbq == 2) return launch_one<Tr, 2, 2>(g, p, w0, w1, s);
-  return launch_one<Tr, 2, 1>(g, p, w0, w1, s);
+  if (g.cbq == 4) return launch_one<Tr, 1, 4>(g, p, w0, w1, s);
+  if (g.cbq == 2) return launch_one<Tr, 1, 2>(g, p, w0, w1, s);
+  return launch_one<Tr, 1, 1>(g, p, w0, w1, s);
 }
 
 int align_up(int v, int a) { return (v + a - 1) / a * a; }
@@ -582,16 +618,16 @@ Mfma2Plan mfma2_plan(const cg_conv_desc& d) {
   for (int cbq = 4; cbq >= 1; cbq >>= 1) {
     if (env_cbq && atoi(env_cbq) != cbq) continue;
     if (cq0 % cbq || (gated && cq1 % cbq)) continue;
-    for (int ngw = 4; ngw >= 2; ngw -= 2) {
+    for (int ngw = 2; ngw >= 1; --ngw) {
       if (env_ngw && atoi(env_ngw) != ngw) continue;
       g.ngw = ngw;
-      g.bm = ngw * 64;
+      g.bm = ngw * 16 * kWaves;
       g.tr = g.bm / wo;
       if (g.tr < 1) continue;
       if (g.tr > rows) g.tr = (int)rows;
       const long long tiles = (rows + g.tr - 1) / g.tr;
       // prefer the large tile only when it still fills the 256 CUs
-      if (ngw == 4 && !env_ngw && tiles * g.n_cb < 256) continue;
+      if (ngw == 2 && !env_ngw && tiles * g.n_cb < 256) continue;
       g.bm_valid = g.tr * wo;
       g.ng = (g.bm_valid + 15) / 16;
       int pr = 0;
@@ -624,12 +660,16 @@ Mfma2Plan mfma2_plan(const cg_conv_desc& d) {
       off += g.max_imgs * kBN * 4;
       if (off > kTabBytes) continue;
 
-      const int sl = cbq == 1 ? 1 : cbq + 1;
+      // plane stride: a multiple of 256 bytes for unit stride, 16 past one for stride 2 (where the
+      // lanes of a group are 32 bytes apart); room for the zero pixel after the npix real ones
+      g.pln = align_up((g.npix + 1) * 16, 256) + (d.stride == 2 ? 16 : 0);
+      g.nps = g.pln / 16;
+      g.magic_nps = magic_of(g.nps);
       g.cbq = cbq;
       g.tsteps = (9 * cbq + 3) / 4;
-      g.kp = (g.npix * sl + kThreads - 1) / kThreads;
+      g.kp = (cbq * g.nps + kThreads - 1) / kThreads;
       if (g.kp > kKP) continue;
-      g.patch_bytes = align_up(g.npix * sl * 16, 1024);
+      g.patch_bytes = align_up(cbq * g.pln, 1024);
       g.w_bytes = g.tsteps * 4 * kBN * 16;
       g.stage_bytes = g.patch_bytes + g.w_bytes;
       if (g.stage_bytes > kStageBytes) continue;
