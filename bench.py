@@ -16,6 +16,7 @@ from __future__ import annotations
 import argparse
 import json
 import os
+import re
 import sys
 import time
 from pathlib import Path
@@ -188,13 +189,12 @@ def main():
         alg_bytes += s.n * s.h * s.w * s.c_in * 2 + s.m * s.c_out * 2 + s.c_out * 9 * s.c_in * 2 + s.m * s.c_out / 8
     t_kernel_us = sum(L["us_gated"] for L in layers)
     achieved = alg_flops / (t_kernel_us * 1e-6) / 1e12
-    traffic = None
-    tfile = ROOT / "profiles" / "traffic.json"
-    if tfile.exists():
-        try:
-            traffic = json.loads(tfile.read_text()).get("bytes_per_launch")
-        except Exception:
-            traffic = None
+    traffic = None     # measured HBM bytes per launch, from the committed counter summary
+    tfile = ROOT / "profiles" / "hbm_traffic_gated_conv_compact_kernel_imagenet_resnet18_bf16_n64.txt"
+    if (tfile.exists() and args.batch == 64 and not args.layers and args.kind == "coherent"
+            and layers[0]["gated"].variant == B.CG_VARIANT_MFMA_COMPACT):
+        m = re.search(r"^bytes_per_launch:\s*(\d+)", tfile.read_text(), re.M)
+        traffic = int(m.group(1)) if m else None
     roofline = dict(bound="mfma", achieved=round(achieved, 2), peak=PEAK_BF16_TFLOPS, unit="TFLOP/s",
                     frac=round(achieved / PEAK_BF16_TFLOPS, 4), traffic=traffic,
                     kernel={B.CG_VARIANT_MFMA: "gated_conv_mfma_kernel<bf16>",

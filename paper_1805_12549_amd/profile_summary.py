@@ -36,5 +36,38 @@ def summarize(db_path: str, command: str = "") -> str:
     return "\n".join(out) + "\n"
 
 
+def traffic(fetch_csv: str, write_csv: str, copy_bytes: int = 256 << 20, kernel: str = "gated_conv") -> str:
+    """HBM bytes per launch of the layer kernel from two counter runs of traffic_probe, each counter
+    scaled by what it reads for the plain copy of known size (the last elementwise copy before the layers)."""
+    import csv
+
+    def read(path, counter):
+        rows = [r for r in csv.DictReader(open(path)) if r["Counter_Name"] == counter]
+        layer = [float(r["Counter_Value"]) for r in rows if kernel in r["Kernel_Name"]]
+        copies = [float(r["Counter_Value"]) for r in rows
+                  if "copy" in r["Kernel_Name"].lower() and abs(int(r["Grid_Size"]) if r.get("Grid_Size") else 1) > 0]
+        big = [v for v in copies if v > 0.5 * max(copies)]
+        return layer, big[-1]
+
+    f_layer, f_copy = read(fetch_csv, "FETCH_SIZE")
+    w_layer, w_copy = read(write_csv, "WRITE_SIZE")
+    f_scale, w_scale = copy_bytes / f_copy, copy_bytes / w_copy
+    out = ["source: rocprofv3 --pmc FETCH_SIZE / --pmc WRITE_SIZE on paper_1805_12549_amd.traffic_probe",
+           "calibration copy of %d bytes: FETCH_SIZE reads %.1f, WRITE_SIZE reads %.1f -> %.2f / %.2f bytes per unit"
+           % (copy_bytes, f_copy, w_copy, f_scale, w_scale),
+           "%-8s %-14s %-14s %-14s" % ("launch", "fetch_bytes", "write_bytes", "total_bytes")]
+    tot = 0.0
+    for i, (f, w) in enumerate(zip(f_layer, w_layer)):
+        fb, wb = f * f_scale, w * w_scale
+        tot += fb + wb
+        out.append("%-8d %-14.0f %-14.0f %-14.0f" % (i, fb, wb, fb + wb))
+    n = max(1, min(len(f_layer), len(w_layer)))
+    out.append("bytes_per_launch: %.0f" % (tot / n))
+    return "\n".join(out) + "\n"
+
+
 if __name__ == "__main__":
-    sys.stdout.write(summarize(sys.argv[1], sys.argv[2] if len(sys.argv) > 2 else ""))
+    if sys.argv[1] == "--traffic":
+        sys.stdout.write(traffic(sys.argv[2], sys.argv[3]))
+    else:
+        sys.stdout.write(summarize(sys.argv[1], sys.argv[2] if len(sys.argv) > 2 else ""))
