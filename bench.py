@@ -40,7 +40,7 @@ def parse():
     ap.add_argument("--no-dense", action="store_true", help="skip the dense comparator (for kernel profiles)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline")
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying a HIP graph")
-    ap.add_argument("--variant", default="auto", choices=["auto", "blockskip", "compact"],
+    ap.add_argument("--variant", default="auto", choices=["auto", "blockskip", "compact", "rows"],
                     help="kernel family (auto = what the library picks)")
     ap.add_argument("--layers", default="", help="comma-separated layer names to restrict the workload")
     return ap.parse_args()
@@ -62,7 +62,8 @@ def main():
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
 
-    variant = {"auto": B.CG_VARIANT_AUTO, "blockskip": B.CG_VARIANT_MFMA, "compact": B.CG_VARIANT_MFMA_COMPACT}[args.variant]
+    variant = {"auto": B.CG_VARIANT_AUTO, "blockskip": B.CG_VARIANT_MFMA, "compact": B.CG_VARIANT_MFMA_COMPACT,
+               "rows": B.CG_VARIANT_MFMA_ROWS}[args.variant]
     shapes = W.imagenet_shapes(n=args.batch)
     if args.layers:
         keep = set(args.layers.split(","))
@@ -198,7 +199,8 @@ def main():
     roofline = dict(bound="mfma", achieved=round(achieved, 2), peak=PEAK_BF16_TFLOPS, unit="TFLOP/s",
                     frac=round(achieved / PEAK_BF16_TFLOPS, 4), traffic=traffic,
                     kernel={B.CG_VARIANT_MFMA: "gated_conv_mfma_kernel<bf16>",
-                            B.CG_VARIANT_MFMA_COMPACT: "gated_conv_compact_kernel<bf16>"}.get(
+                            B.CG_VARIANT_MFMA_COMPACT: "gated_conv_compact_kernel<bf16>",
+                            B.CG_VARIANT_MFMA_ROWS: "gated_conv_rows_kernel<bf16>"}.get(
                                 layers[0]["gated"].variant, "naive_kernel"), avg_launch_us=round(t_kernel_us / len(layers), 2),
                     algorithmic_gflop_per_launch=round(alg_flops / len(layers) / 1e9, 3),
                     hbm_gbs_algorithmic=round(alg_bytes / (t_kernel_us * 1e-6) / 1e9, 1),

@@ -45,10 +45,16 @@ typedef struct cg_conv cg_conv; /* opaque */
 enum { CG_OK = 0, CG_EINVAL = 1, CG_EUNSUPPORTED = 2, CG_ENOMEM = 3, CG_EHIP = 4 };
 enum { CG_F32 = 0, CG_BF16 = 1, CG_I8 = 2, CG_I32 = 3 };
 enum { CG_EPI_RELU = 1u, CG_EPI_AFFINE = 2u, CG_EPI_RESIDUAL = 4u };
-/* Kernel family.  AUTO picks the pixel-compacting matrix-core kernel when the shape allows,
- * else the block-skipping matrix-core kernel, else the plain one-thread-per-activation kernel.
- * All three compute the same layer. */
-enum { CG_VARIANT_AUTO = 0, CG_VARIANT_NAIVE = 1, CG_VARIANT_MFMA = 2, CG_VARIANT_MFMA_COMPACT = 3 };
+/* Kernel family.  AUTO picks the row-tiled pixel-compacting matrix-core kernel when the shape
+ * allows, else the older pixel-compacting one, else the block-skipping matrix-core kernel, else
+ * the plain one-thread-per-activation kernel.  All of them compute the same layer. */
+enum {
+  CG_VARIANT_AUTO = 0,
+  CG_VARIANT_NAIVE = 1,
+  CG_VARIANT_MFMA = 2,
+  CG_VARIANT_MFMA_COMPACT = 3,
+  CG_VARIANT_MFMA_ROWS = 4
+};
 
 typedef struct cg_conv_desc {
   uint32_t struct_size;      /* = sizeof(cg_conv_desc); checked */

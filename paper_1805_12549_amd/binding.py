@@ -46,7 +46,7 @@ if len(_hip_runtimes_mapped()) > 1:
 CG_OK, CG_EINVAL, CG_EUNSUPPORTED, CG_ENOMEM, CG_EHIP = 0, 1, 2, 3, 4
 CG_F32, CG_BF16, CG_I8, CG_I32 = 0, 1, 2, 3
 CG_EPI_RELU, CG_EPI_AFFINE, CG_EPI_RESIDUAL = 1, 2, 4
-CG_VARIANT_AUTO, CG_VARIANT_NAIVE, CG_VARIANT_MFMA, CG_VARIANT_MFMA_COMPACT = 0, 1, 2, 3
+CG_VARIANT_AUTO, CG_VARIANT_NAIVE, CG_VARIANT_MFMA, CG_VARIANT_MFMA_COMPACT, CG_VARIANT_MFMA_ROWS = 0, 1, 2, 3, 4
 
 EXPORTS = ("cg_conv_packed_bytes", "cg_conv_create", "cg_conv_workspace_bytes", "cg_conv_forward",
            "cg_conv_destroy", "cg_conv_info", "cg_last_error")

@@ -57,6 +57,7 @@ struct cg_conv {
   int variant;              // resolved CG_VARIANT_*
   cg::MfmaPlan plan;
   cg::Mfma2Plan plan2;
+  cg::Mfma3Plan plan3;
   Layout lay;
   std::vector<uint32_t> staging;  // host image of the tables; kept alive for the async copy
 };
@@ -87,7 +88,7 @@ int validate(const cg_conv_desc* d, int* ho, int* wo) {
   }
   if (d->epilogue & ~(CG_EPI_RELU | CG_EPI_AFFINE | CG_EPI_RESIDUAL)) return fail(CG_EINVAL, "unknown epilogue flag");
   if (d->variant != CG_VARIANT_AUTO && d->variant != CG_VARIANT_NAIVE && d->variant != CG_VARIANT_MFMA &&
-      d->variant != CG_VARIANT_MFMA_COMPACT)
+      d->variant != CG_VARIANT_MFMA_COMPACT && d->variant != CG_VARIANT_MFMA_ROWS)
     return fail(CG_EINVAL, "unknown variant %d", d->variant);
   if (d->x_pixel_stride != 0 && d->x_pixel_stride < d->c_in)
     return fail(CG_EINVAL, "x_pixel_stride must be 0 or >= c_in");
@@ -144,6 +145,7 @@ Layout make_layout(const cg_conv_desc& d, size_t wpk_base_bytes, size_t wpk_cond
 struct Plans {
   cg::MfmaPlan v1;
   cg::Mfma2Plan v2;
+  cg::Mfma3Plan v3;
   int variant;
   size_t wpk_base_bytes, wpk_cond_bytes;
 };
@@ -151,15 +153,28 @@ struct Plans {
 int resolve_variant(const cg_conv_desc& d, Plans* pl) {
   pl->v1 = cg::mfma_plan(d);
   pl->v2 = cg::mfma2_plan(d);
+  pl->v3 = cg::mfma3_plan(d);
   if (d.variant == CG_VARIANT_MFMA && !pl->v1.ok)
     return fail(CG_EUNSUPPORTED, "the block-skipping matrix-core kernel does not cover this shape/dtype");
   if (d.variant == CG_VARIANT_MFMA_COMPACT && !pl->v2.ok)
     return fail(CG_EUNSUPPORTED, "the pixel-compacting matrix-core kernel does not cover this shape/dtype");
+  if (d.variant == CG_VARIANT_MFMA_ROWS && !pl->v3.ok)
+    return fail(CG_EUNSUPPORTED, "the row-tiled matrix-core kernel does not cover this shape/dtype");
   int v = d.variant;
-  if (v == CG_VARIANT_AUTO) v = pl->v2.ok ? CG_VARIANT_MFMA_COMPACT : pl->v1.ok ? CG_VARIANT_MFMA : CG_VARIANT_NAIVE;
+  if (v == CG_VARIANT_AUTO)
+    v = pl->v3.ok   ? CG_VARIANT_MFMA_ROWS
+        : pl->v2.ok ? CG_VARIANT_MFMA_COMPACT
+        : pl->v1.ok ? CG_VARIANT_MFMA
+                    : CG_VARIANT_NAIVE;
   pl->variant = v;
-  pl->wpk_base_bytes = v == CG_VARIANT_MFMA_COMPACT ? pl->v2.wpk_base_bytes : v == CG_VARIANT_MFMA ? pl->v1.wpk_base_bytes : 0;
-  pl->wpk_cond_bytes = v == CG_VARIANT_MFMA_COMPACT ? pl->v2.wpk_cond_bytes : v == CG_VARIANT_MFMA ? pl->v1.wpk_cond_bytes : 0;
+  pl->wpk_base_bytes = v == CG_VARIANT_MFMA_ROWS      ? pl->v3.wpk_base_bytes
+                       : v == CG_VARIANT_MFMA_COMPACT ? pl->v2.wpk_base_bytes
+                       : v == CG_VARIANT_MFMA         ? pl->v1.wpk_base_bytes
+                                                      : 0;
+  pl->wpk_cond_bytes = v == CG_VARIANT_MFMA_ROWS      ? pl->v3.wpk_cond_bytes
+                       : v == CG_VARIANT_MFMA_COMPACT ? pl->v2.wpk_cond_bytes
+                       : v == CG_VARIANT_MFMA         ? pl->v1.wpk_cond_bytes
+                                                      : 0;
   return CG_OK;
 }
 
@@ -180,6 +195,10 @@ size_t cg_conv_packed_bytes(const cg_conv_desc* desc) {
   if (validate(desc, &ho, &wo) != CG_OK) return 0;
   Plans pl;
   if (resolve_variant(*desc, &pl) != CG_OK) return 0;
+  if (getenv("CG_DEBUG") && pl.v3.ok)
+    fprintf(stderr, "[cg_conv] rows plan: nf=%d bm=%d n_cb=%d tr=%d pitch=%d pr=%d cps=%d ni=%d pkb=%d stages=%d,%d\n",
+            pl.v3.nf, pl.v3.bm, pl.v3.n_cb, pl.v3.tr, 1 << pl.v3.logp, pl.v3.pr, pl.v3.cps, pl.v3.ni, pl.v3.pkb,
+            pl.v3.stages[0], pl.v3.stages[1]);
   return make_layout(*desc, pl.wpk_base_bytes, pl.wpk_cond_bytes).total;
 }
 
@@ -196,6 +215,7 @@ int cg_conv_create(cg_conv** out, const cg_conv_desc* desc, void* hip_stream) {
   const int variant = pl.variant;
   const cg::MfmaPlan& plan = pl.v1;
   const cg::Mfma2Plan& plan2 = pl.v2;
+  const cg::Mfma3Plan& plan3 = pl.v3;
   const Layout lay = make_layout(d, pl.wpk_base_bytes, pl.wpk_cond_bytes);
   if (getenv("CG_DEBUG"))
     fprintf(stderr,
@@ -211,6 +231,10 @@ int cg_conv_create(cg_conv** out, const cg_conv_desc* desc, void* hip_stream) {
             plan2.ngw, plan2.bm, plan2.n_cb, plan2.tr, plan2.pr_max, plan2.pw, plan2.npix, plan2.bm_valid, plan2.ng,
             plan2.max_imgs, plan2.cbq, plan2.stages[0], plan2.stages[1], plan2.tsteps, plan2.kp, plan2.stage_bytes,
             plan2.lds_total);
+  if (getenv("CG_DEBUG") && plan3.ok)
+    fprintf(stderr, "[cg_conv] rows plan: nf=%d bm=%d n_cb=%d tr=%d pitch=%d pr=%d cps=%d ni=%d pkb=%d stages=%d,%d\n",
+            plan3.nf, plan3.bm, plan3.n_cb, plan3.tr, 1 << plan3.logp, plan3.pr, plan3.cps, plan3.ni, plan3.pkb,
+            plan3.stages[0], plan3.stages[1]);
   if (!d.packed) return fail(CG_EINVAL, "packed is NULL");
   if (((uintptr_t)d.packed & 255) != 0) return fail(CG_EINVAL, "packed must be 256-byte aligned");
   if (d.packed_bytes < lay.total)
@@ -226,6 +250,7 @@ int cg_conv_create(cg_conv** out, const cg_conv_desc* desc, void* hip_stream) {
   h->variant = variant;
   h->plan = plan;
   h->plan2 = plan2;
+  h->plan3 = plan3;
   h->lay = lay;
 
   // Host image of the per-channel tables.
@@ -280,7 +305,7 @@ int cg_conv_create(cg_conv** out, const cg_conv_desc* desc, void* hip_stream) {
     e = hipMemcpyAsync(pk + lay.w_base_off, d.w_base, lay.w_base_bytes, hipMemcpyDeviceToDevice, s);
   if (e == hipSuccess && lay.w_cond_bytes)
     e = hipMemcpyAsync(pk + lay.w_cond_off, d.w_cond, lay.w_cond_bytes, hipMemcpyDeviceToDevice, s);
-  if (e == hipSuccess && (variant == CG_VARIANT_MFMA || variant == CG_VARIANT_MFMA_COMPACT)) {
+  if (e == hipSuccess && variant != CG_VARIANT_NAIVE) {
     cg::Params p{};
     p.c_in = d.c_in;
     p.c_out = d.c_out;
@@ -293,8 +318,10 @@ int cg_conv_create(cg_conv** out, const cg_conv_desc* desc, void* hip_stream) {
     p.w_cond = pk + lay.w_cond_off;
     if (variant == CG_VARIANT_MFMA)
       e = cg::launch_mfma_pack(plan, p, pk + lay.wpk_base_off, pk + lay.wpk_cond_off, s);
-    else
+    else if (variant == CG_VARIANT_MFMA_COMPACT)
       e = cg::launch_mfma2_pack(plan2, p, pk + lay.wpk_base_off, pk + lay.wpk_cond_off, s);
+    else
+      e = cg::launch_mfma3_pack(plan3, p, pk + lay.wpk_base_off, pk + lay.wpk_cond_off, s);
   }
   if (e != hipSuccess) {
     const int code = fail(CG_EHIP, "cg_conv_create: %s", hipGetErrorString(e));
@@ -307,8 +334,11 @@ int cg_conv_create(cg_conv** out, const cg_conv_desc* desc, void* hip_stream) {
 }
 
 size_t cg_conv_workspace_bytes(const cg_conv* h, int32_t n) {
-  (void)n;
-  if (!h) return 0;
+  if (!h || n <= 0) return 0;
+  // the row-tiled kernel counts fired gates from the decision bitmap; when the caller asks for
+  // counts without a bitmap the bitmap is written to the workspace
+  if (h->variant == CG_VARIANT_MFMA_ROWS && h->c_cond > 0)
+    return align256((size_t)n * h->ho * h->wo * ((h->d.c_out + 31) / 32) * 4);
   return 0;
 }
 
@@ -391,7 +421,16 @@ int cg_conv_forward(cg_conv* h, int32_t n, const void* x, const void* residual, 
   hipStream_t s = (hipStream_t)hip_stream;
   hipError_t e = hipSuccess;
   if (counts) e = cg::launch_zero_u32(counts, 2 + (size_t)n * d.c_out, s);
-  if (e == hipSuccess) {
+  if (e == hipSuccess && h->variant == CG_VARIANT_MFMA_ROWS) {
+    const size_t bm_words = (size_t)p.m_total * p.words;
+    if (!p.gated) {
+      if (bitmap) e = cg::launch_zero_u32(bitmap, bm_words, s);   // a dense layer has no decisions
+    } else if (counts && !bitmap) {
+      p.bitmap = (uint32_t*)workspace;
+    }
+    if (e == hipSuccess) e = cg::launch_mfma3(h->plan3, p, pk + l.wpk_base_off, pk + l.wpk_cond_off, s);
+    if (e == hipSuccess && counts && p.gated && !(p.debug & 16)) e = cg::launch_bitmap_counts(p, p.bitmap, s);
+  } else if (e == hipSuccess) {
     if (h->variant == CG_VARIANT_MFMA_COMPACT)
       e = cg::launch_mfma2(h->plan2, p, pk + l.wpk_base_off, pk + l.wpk_cond_off, s);
     else if (h->variant == CG_VARIANT_MFMA)

@@ -109,6 +109,37 @@ hipError_t launch_mfma2_pack(const Mfma2Plan& plan, const Params& p, void* wpk_b
 hipError_t launch_mfma2(const Mfma2Plan& plan, const Params& p, const void* wpk_base, const void* wpk_cond,
                         hipStream_t s);
 
+// Geometry of the row-tiled matrix-core kernel (32x32 MFMA blocks, transposed product).
+//
+// Tiles are `tr` consecutive global output rows x 64 channels as above.  K is walked in super-stages
+// of `cps` 16-byte channel chunks per pixel; the LDS patch of a super-stage holds 16*cps bytes per
+// pixel slot, slot = patch_row * 2^logp + (wi + pad).
+struct Mfma3Plan {
+  int ok;
+  int elem_bytes, ch;      // bytes per element; channels per 16-byte chunk
+  int nf;                  // 32-pixel fragments per wavefront in the base phase (1 or 2)
+  int bm;                  // 128*nf pixels per tile, padded
+  int n_cb;                // c_out / 64
+  int tr;                  // global output rows per tile
+  int hp;                  // h + 2*pad
+  unsigned magic_hp, magic_ho, magic_wo;
+  int logp;                // log2 of the patch row pitch in pixel slots (pitch >= 16, > w + pad - 1)
+  int pr;                  // patch rows, maximum over tiles
+  int cps;                 // chunks per pixel per super-stage: 4 or 2
+  int ni;                  // 1 KB load instructions per super-stage patch = ceil(pr * pitch * cps / 64)
+  int pkb;                 // LDS patch buffer class: 24 KB (two workgroups per CU) or 48 KB
+  int stages[2];           // super-stages of the base / conditional phase
+  int phase_sleep;         // start delay (units of 512 cycles) of every other round of workgroups
+  size_t wpk_base_bytes, wpk_cond_bytes;
+};
+
+Mfma3Plan mfma3_plan(const cg_conv_desc& d);
+hipError_t launch_mfma3_pack(const Mfma3Plan& plan, const Params& p, void* wpk_base, void* wpk_cond, hipStream_t s);
+hipError_t launch_mfma3(const Mfma3Plan& plan, const Params& p, const void* wpk_base, const void* wpk_cond,
+                        hipStream_t s);
+// per-(image, channel) fired counts and their total (into p.counts, total pre-zeroed) from a decision bitmap
+hipError_t launch_bitmap_counts(const Params& p, const uint32_t* bitmap, hipStream_t s);
+
 // launchers (return hipError_t from the last launch)
 hipError_t launch_naive(const Params& p, hipStream_t s);
 hipError_t launch_zero_u32(uint32_t* ptr, size_t words, hipStream_t s);

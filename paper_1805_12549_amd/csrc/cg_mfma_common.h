@@ -35,12 +35,15 @@ struct I8Traits {
 
 __device__ __forceinline__ int shfl_xor_i(int v, int mask) { return __shfl_xor(v, mask, 64); }
 
-// Output function for eight consecutive channels co0..co0+7 of one output pixel.
+// Output function for eight consecutive channels co0..co0+7 of one output pixel, into registers.
 // s0, s1: the eight sums (fp32 bit patterns or int32); dbyte: their decisions, bit k = channel co0+k;
-// o: element offset of channel co0 in y / residual.
+// o: element offset of channel co0 in y / residual.  The converted values come back packed in
+// out0 (and out1 for 4-byte outputs): 32 bytes for CG_F32 / CG_I32, 16 for CG_BF16, 8 for CG_I8.
 template <typename Tr>
-__device__ __forceinline__ void finish_store8(const Params& p, i32x4 s0, i32x4 s1, uint32_t dbyte, int co0,
-                                              long long o) {
+__device__ __forceinline__ void finish8(const Params& p, i32x4 s0, i32x4 s1, uint32_t dbyte, int co0, long long o,
+                                        i32x4& out0, i32x4& out1) {
+  out0 = i32x4{0, 0, 0, 0};
+  out1 = i32x4{0, 0, 0, 0};
   if constexpr (Tr::kDtype == CG_I8) {
     int32_t v[8];
     int8_t res8[8] = {0, 0, 0, 0, 0, 0, 0, 0};
@@ -69,13 +72,11 @@ __device__ __forceinline__ void finish_store8(const Params& p, i32x4 s0, i32x4 s
       }
     }
     if (p.out_dtype == CG_I32) {
-      *(i32x4*)((int32_t*)p.y + o) = i32x4{v[0], v[1], v[2], v[3]};
-      *(i32x4*)((int32_t*)p.y + o + 4) = i32x4{v[4], v[5], v[6], v[7]};
+      out0 = i32x4{v[0], v[1], v[2], v[3]};
+      out1 = i32x4{v[4], v[5], v[6], v[7]};
     } else {
-      int8_t b8[8];
-#pragma unroll
-      for (int k = 0; k < 8; ++k) b8[k] = (int8_t)v[k];
-      *(uint2*)((int8_t*)p.y + o) = *(const uint2*)b8;
+      out0[0] = (v[0] & 0xff) | ((v[1] & 0xff) << 8) | ((v[2] & 0xff) << 16) | ((v[3] & 0xff) << 24);
+      out0[1] = (v[4] & 0xff) | ((v[5] & 0xff) << 8) | ((v[6] & 0xff) << 16) | ((v[7] & 0xff) << 24);
     }
   } else {
     float v[8];
@@ -108,14 +109,32 @@ __device__ __forceinline__ void finish_store8(const Params& p, i32x4 s0, i32x4 s
       v[k] = a;
     }
     if (p.out_dtype == CG_F32) {
-      *(f32x4*)((float*)p.y + o) = f32x4{v[0], v[1], v[2], v[3]};
-      *(f32x4*)((float*)p.y + o + 4) = f32x4{v[4], v[5], v[6], v[7]};
-    } else {
-      uint16_t ob[8];
 #pragma unroll
-      for (int k = 0; k < 8; ++k) ob[k] = float_to_bf16(v[k]);
-      *(i32x4*)((uint16_t*)p.y + o) = *(const i32x4*)ob;
+      for (int k = 0; k < 4; ++k) {
+        out0[k] = __float_as_int(v[k]);
+        out1[k] = __float_as_int(v[k + 4]);
+      }
+    } else {
+#pragma unroll
+      for (int k = 0; k < 4; ++k)
+        out0[k] = (int)((uint32_t)float_to_bf16(v[2 * k]) | ((uint32_t)float_to_bf16(v[2 * k + 1]) << 16));
     }
+  }
+}
+
+// the same, stored to y
+template <typename Tr>
+__device__ __forceinline__ void finish_store8(const Params& p, i32x4 s0, i32x4 s1, uint32_t dbyte, int co0,
+                                              long long o) {
+  i32x4 a, b;
+  finish8<Tr>(p, s0, s1, dbyte, co0, o, a, b);
+  if (p.out_dtype == CG_F32 || p.out_dtype == CG_I32) {
+    *(i32x4*)((int32_t*)p.y + o) = a;
+    *(i32x4*)((int32_t*)p.y + o + 4) = b;
+  } else if (p.out_dtype == CG_BF16) {
+    *(i32x4*)((uint16_t*)p.y + o) = a;
+  } else {
+    *(int2*)((int8_t*)p.y + o) = int2{a[0], a[1]};
   }
 }
 

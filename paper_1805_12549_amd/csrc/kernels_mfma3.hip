@@ -1,0 +1,917 @@
+// Row-tiled matrix-core kernel of the gated convolution (bf16 and int8 MFMA, 32x32 blocks).
+//
+// One workgroup of four wavefronts owns BM = 128 or 256 consecutive output pixels (whole output
+// rows of the batch, numbered R = img*Ho + ho, possibly straddling images) times 64 output
+// channels and runs the whole layer for them (Eq. 1 of the channel-gating paper).  Two workgroups
+// share a compute unit when the input patch is small enough.
+//
+//   base path   implicit GEMM over taps x base channels.  Each wavefront owns NF 32-pixel
+//               fragments x 64 channels.  The product is taken transposed (weights as the row
+//               operand, pixels as the column operand), which leaves every lane with 16
+//               consecutive channels of one pixel per accumulator: gate and output function
+//               work on registers.
+//   gate        accumulators against the per-channel thresholds (merged gate, Sec. 3.2); each
+//               lane packs its 32 decisions; the decision words of the tile meet in LDS and leave
+//               as one coalesced store.
+//   compaction  ballot / prefix sum over the pixels with a fired gate lists them; 32-pixel
+//               fragments of that list are dealt to the wavefronts.
+//   cond. path  the same MFMA loop over taps x remaining channels on the listed pixels only
+//               (the pixel operand is gathered from the LDS patch by per-lane address).
+//   combine     R goes through a small LDS tile back to the lanes that hold P; S = P + d*R, then
+//               scale/shift by decision, residual, ReLU, convert (Eq. 1); 2-byte and 1-byte
+//               outputs are transposed through LDS so that every store covers whole pixel rows.
+//
+// Global -> LDS traffic is the scarce resource (one cache line per clock per CU, whatever part of
+// the line is used), so the input patch is fetched CPS 16-byte channel chunks per pixel at a time
+// (CPS = 4: 64 contiguous bytes per pixel and load-instruction quad), one "super-stage" of K, and
+// kept in LDS as [pixel slot][CPS chunk positions]; chunk q of slot s sits at position q ^ f(s),
+// f(s) = (s >> 2) & 3 (CPS = 4) or (s >> 3) & 1 (CPS = 2), which makes the 16-lane operand reads
+// conflict-free.  Slot = patch_row * P + c with P a power of two >= max(16, W + pad) and
+// c = wi + pad, so the zero padding left and right of a row are the never-loaded slots between
+// rows; rows outside the image are zeroed once.  Weights stream through a two-deep ring of
+// granules, one kernel row (three taps) of the super-stage each; granule g+1 and a part of the
+// next super-stage's patch are fetched by LDS-direct loads while granule g is multiplied.
+#include <cstdlib>
+#include <type_traits>
+
+#include "cg_mfma_common.h"
+
+namespace cg {
+
+namespace {
+
+constexpr int kWv = 4;                       // wavefronts per workgroup
+constexpr int kTh = kWv * 64;
+constexpr int kBn = 64;                      // output channels per workgroup
+constexpr int kTab = 5 * 1024;
+constexpr int kRs = 272;                     // bytes per row of the R tile: 64 sums + 16 bytes of skew
+
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(16))) int i32x16;
+
+// 32x32 output block; lane l supplies row / column l%32 and the 16-byte K chunk l/32 of either
+// operand; it receives column l%32, rows 8*(i/4) + 4*(l/32) + i%4 in register i.
+struct Bf16Rows {
+  using Base = Bf16Traits;
+  using acc16 = f32x16;
+  using acc_t = float;
+  static __device__ __forceinline__ acc16 mfma(i32x4 rows, i32x4 cols, acc16 c) {
+    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, rows), __builtin_bit_cast(bf16x8, cols),
+                                                   c, 0, 0, 0);
+  }
+};
+
+struct I8Rows {
+  using Base = I8Traits;
+  using acc16 = i32x16;
+  using acc_t = int32_t;
+  static __device__ __forceinline__ acc16 mfma(i32x4 rows, i32x4 cols, acc16 c) {
+    return __builtin_amdgcn_mfma_i32_32x32x32_i8(rows, cols, c, 0, 0, 0);
+  }
+};
+
+// bit patterns of accumulator elements (a bit cast applied directly to an element of a vector
+// register array reads element 0 with this compiler, so the value is copied to a scalar first)
+__device__ __forceinline__ int as_bits(float f) { return __float_as_int(f); }
+__device__ __forceinline__ int as_bits(int v) { return v; }
+__device__ __forceinline__ void from_bits(int b, float& f) { f = __int_as_float(b); }
+__device__ __forceinline__ void from_bits(int b, int& v) { v = b; }
+
+__device__ __forceinline__ int fdiv3(int x, unsigned magic) { return (int)__umulhi((unsigned)x, magic); }
+
+__device__ __forceinline__ void lds_direct16(const char* gsrc, char* ldst) {
+  // each active lane copies 16 bytes from its own global address to ldst + lane*16
+  __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)gsrc,
+                                   (__attribute__((address_space(3))) void*)ldst, 16, 0, 0);
+}
+
+// 16-byte LDS read the compiler does not see as a memory access: it then neither orders it against
+// the LDS-direct loads in flight nor waits for it; the caller waits (lgkmcnt) before using the value
+__device__ __forceinline__ i32x4 lds_read16(const char* p) {
+  i32x4 v;
+  const unsigned addr = (unsigned)(uintptr_t)p;     // low half of a generic LDS address = LDS byte offset
+  asm volatile("ds_read_b128 %0, %1" : "=v"(v) : "v"(addr) : "memory");
+  return v;
+}
+
+// s_waitcnt vmcnt(n), n <= 6: at most n vector-memory operations of this wavefront still in flight
+__device__ __forceinline__ void wait_vm(int n) {
+  switch (n) {
+    case 0: __builtin_amdgcn_s_waitcnt(0x0F70); break;
+    case 1: __builtin_amdgcn_s_waitcnt(0x0F71); break;
+    case 2: __builtin_amdgcn_s_waitcnt(0x0F72); break;
+    case 3: __builtin_amdgcn_s_waitcnt(0x0F73); break;
+    case 4: __builtin_amdgcn_s_waitcnt(0x0F74); break;
+    case 5: __builtin_amdgcn_s_waitcnt(0x0F75); break;
+    case 6: __builtin_amdgcn_s_waitcnt(0x0F76); break;
+    default: __builtin_amdgcn_s_waitcnt(0x0F70); break;
+  }
+}
+
+// byte offset of chunk position (h ^ f(slot)) of pixel slot `slot`: the chunk lane half h multiplies
+// in the first chunk pair of a super-stage; the second pair (CPS = 4) is 32 bytes away by XOR
+template <int CPS>
+__device__ __forceinline__ int slot_addr(int slot, int h) {
+  if constexpr (CPS == 4) return slot * 64 + ((h ^ (slot >> 2)) & 3) * 16;
+  return slot * 32 + ((h ^ (slot >> 3)) & 1) * 16;
+}
+
+// One weight granule of MFMAs for this wavefront: NL pixel fragments x two 32-channel fragments,
+// GK = 3*CPS/2 K steps (three taps of one kernel row x CPS/2 chunk pairs).  ar[fp][c] is the lane's
+// patch byte offset of fragment fp at tap column c in this kernel row; wofs the lane's offset of
+// its weight rows.  The operand reads of step k+1 and a slice of the prefetch (issue(k)) are
+// interleaved with the MFMAs of step k; the scheduling barriers pin that order.
+template <typename Tr, int NL, int NFM, int CPS, typename IssueFn>
+__device__ __forceinline__ void mma_granule(const char* __restrict__ pat, const char* __restrict__ wg, int wofs,
+                                            const int (&ar)[NFM][3], typename Tr::acc16 (&acc)[NFM][2],
+                                            IssueFn&& issue, int knob = 0) {
+  constexpr int GK = 3 * CPS / 2;
+  constexpr int PAIRS = CPS / 2;
+  constexpr int M = NL * 2;   // MFMAs per K step
+  i32x4 a[2][2], b[2][NL > 0 ? NL : 1];
+  if constexpr (NL > 0) {
+#pragma unroll
+    for (int fc = 0; fc < 2; ++fc) a[0][fc] = lds_read16(wg + wofs + fc * 512);
+#pragma unroll
+    for (int fp = 0; fp < NL; ++fp) b[0][fp] = lds_read16(pat + ar[fp][0]);
+  }
+#pragma unroll
+  for (int k = 0; k < GK; ++k) {
+    if constexpr (NL == 0) {
+      issue(k);
+    } else {
+      const int c = k & 1, n = c ^ 1;
+      __builtin_amdgcn_s_waitcnt(0xC07F);   // lgkmcnt(0): operands of step k are in registers
+      __builtin_amdgcn_sched_barrier(0);
+      // all operand reads of step k+1 go out before the MFMAs of step k: they then have the whole
+      // step to land
+      if (k + 1 < GK && !(knob & 2)) {
+#pragma unroll
+        for (int i = 0; i < 2; ++i) a[n][i] = lds_read16(wg + wofs + (k + 1) * 2048 + i * 512);
+#pragma unroll
+        for (int i = 0; i < NL; ++i)
+          b[n][i] = lds_read16(pat + (ar[i][(k + 1) / PAIRS] ^ (((k + 1) % PAIRS) * 32)));
+      }
+      __builtin_amdgcn_sched_barrier(0);
+      if (!(knob & 1)) acc[0][0] = Tr::mfma(a[c][0], b[c][0], acc[0][0]);
+      __builtin_amdgcn_sched_barrier(0);
+      issue(k);
+      __builtin_amdgcn_sched_barrier(0);
+      if (!(knob & 1)) {
+#pragma unroll
+        for (int j = 1; j < M; ++j) acc[j >> 1][j & 1] = Tr::mfma(a[c][j & 1], b[c][j >> 1], acc[j >> 1][j & 1]);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  }
+}
+
+template <typename Tr, int NF, int CPS, int PKB>
+__global__ __launch_bounds__(kTh, PKB == 24 ? 2 : 1) void gated_conv_rows_kernel(Params p, Mfma3Plan g,
+                                                                                const char* __restrict__ wpk0,
+                                                                                const char* __restrict__ wpk1) {
+  using acc16 = typename Tr::acc16;
+  using acc_t = typename Tr::acc_t;
+  using Base = typename Tr::Base;
+  constexpr int GK = 3 * CPS / 2;              // K steps per weight granule
+  constexpr int GB = GK * 2048;                // bytes per weight granule
+  constexpr int PB = PKB * 1024;               // bytes per patch buffer
+  constexpr int SB = 16 * CPS;                 // bytes per pixel slot
+  constexpr int KPW = PB / 1024 / kWv;         // patch load instructions per wavefront per super-stage, at most
+  constexpr int KH = (KPW + 1) / 2;            // of which in the first granule; the rest in the second
+  constexpr int WPW = (2 * GK + kWv - 1) / kWv;   // weight load instructions per wavefront per granule
+  constexpr int BM = 128 * NF;
+  static_assert(KH <= 6, "vmcnt wait table");
+
+  // two patch buffers, two weight granule buffers, tables
+  __shared__ __align__(1024) char pat2[2 * PB];
+  __shared__ __align__(1024) char wgt2[2 * GB];
+  __shared__ __align__(16) char smem[kTab];
+  char* const patA = pat2;
+  char* const patB = pat2 + PB;
+  char* const wgtA = wgt2;
+  int* pslot = (int*)smem;                       // [256] tile pixel -> patch slot of its tap (0,0)
+  int* clist = pslot + 256;                      // [256] compacted position -> patch slot
+  uint16_t* rank = (uint16_t*)(clist + 256);     // [256] tile pixel -> compacted position
+  acc_t* tlo = (acc_t*)(rank + 256);             // [64] thresholds of this channel block
+  acc_t* thi = tlo + 64;
+  uint32_t* bmp = (uint32_t*)(thi + 64);         // [256][2] decision words of the tile
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int lj = lane & 31, lh = lane >> 5;
+
+  // blocks that share a pixel tile (different channel blocks) sit on the same XCD (block id mod 8)
+  int tile, cbk;
+  {
+    const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+    const int grp = slot / g.n_cb;
+    cbk = slot - grp * g.n_cb;
+    tile = grp * 8 + xcd;
+  }
+  const int total_rows = p.n * p.ho;
+  const int R0 = tile * g.tr;
+  if (R0 >= total_rows) return;
+#ifdef CG_PROFILE_KNOBS
+  // developer builds: cycle stamps of two workgroups, kept in LDS and copied to the counts buffer at
+  // the end (results are then wrong)
+  __shared__ long long stampbuf[32];
+  const bool stamp = (p.debug & 16) && p.counts && tid == 0 && (blockIdx.x == 0 || blockIdx.x == gridDim.x / 2 + 1);
+  int n_stamp = 0;
+#define CG_STAMP()                                                 \
+  do {                                                             \
+    if (stamp && n_stamp < 32) stampbuf[n_stamp++] = clock64();    \
+  } while (0)
+#define CG_KNOB p.debug
+#else
+#define CG_STAMP() do {} while (0)
+#define CG_KNOB 0
+#endif
+  CG_STAMP();
+  if (CG_KNOB & 256) return;
+  // The two workgroups that share a CU (block ids 256 apart when every CU receives one block per
+  // round) would run their load / multiply / store phases in lockstep and leave the matrix cores
+  // idle in between; delaying every other round by roughly half a granule offsets them.
+  if (g.phase_sleep > 0 && ((blockIdx.x >> 8) & 1)) {
+    for (int i = 0; i < g.phase_sleep; ++i) __builtin_amdgcn_s_sleep(8);
+  }
+
+  const int S0 = g.stages[0];                       // super-stages of the base phase
+  const int S = S0 + (p.gated ? g.stages[1] : 0);
+  int G = 3 * S;                                    // weight granules
+  const int eb = g.elem_bytes;
+
+  // gate thresholds of this channel block: the loads go out first, the LDS copy follows later
+  acc_t my_lo = 0, my_hi = 0;
+  if (tid < 64) {
+    const int co = cbk * kBn + tid;
+    if constexpr (Base::kDtype == CG_I8) {
+      my_lo = p.thr_i[co];
+    } else {
+      my_lo = p.thr_f[co];
+      my_hi = p.thr_hi_f[co];
+    }
+  }
+
+  // source of weight granule gi (3*sigma + r) of this channel block
+  auto w_src = [&](int gi) __attribute__((always_inline)) {
+    const int ph = gi >= 3 * S0 ? 1 : 0;
+    const int gg = ph ? gi - 3 * S0 : gi;
+    return (ph ? wpk1 : wpk0) + ((size_t)cbk * 3 * g.stages[ph] + gg) * GB;
+  };
+  // weight load instruction u of this wavefront: 1 KB number wave + 4u of the granule
+  auto issue_w = [&](const char* ws, char* dst, int u) __attribute__((always_inline)) {
+    const int idx = wave + kWv * u;
+    if (idx < 2 * GK) lds_direct16(ws + idx * 1024 + lane * 16, dst + idx * 1024);
+  };
+  {
+    const char* ws0 = w_src(0);
+#pragma unroll
+    for (int u = 0; u < WPW; ++u) issue_w(ws0, wgtA, u);
+  }
+
+  const long long m0 = (long long)R0 * p.wo;        // first output pixel
+  const int rows_here = total_rows - R0 < g.tr ? total_rows - R0 : g.tr;
+  const int bmv = rows_here * p.wo;                 // output pixels of this tile
+  const int img0 = fdiv3(R0, g.magic_ho);
+  const int rho0 = img0 * g.hp + (R0 - img0 * p.ho) * p.stride;   // stacked padded input row of patch row 0
+  const int rowb = SB << g.logp;                    // bytes per patch row
+
+  // ---- this wavefront's patch load instructions: instruction idx = wave + 4k fills the 64 chunk
+  // positions [64*idx, +64), i.e. 64/CPS pixel slots; a lane outside the image keeps a zero that is
+  // written once.  smask bit k: the instruction has at least one lane inside the image.
+  const char* xbytes = (const char*)p.x;
+  const int xps = (int)p.x_pixel_stride * eb;
+  int voff[KPW];
+  unsigned smask = 0u;
+#pragma unroll
+  for (int k = 0; k < KPW; ++k) {
+    voff[k] = -1;
+    const int idx = wave + kWv * k;
+    if (idx < g.ni) {
+      const int pos16 = idx * 64 + lane;
+      const int sl = pos16 / CPS, cp = pos16 % CPS;
+      const int f = CPS == 4 ? (sl >> 2) & 3 : (sl >> 3) & 1;
+      const int q = cp ^ f;
+      const int prow = sl >> g.logp, c = sl & ((1 << g.logp) - 1);
+      const int rho = rho0 + prow;
+      const int img = fdiv3(rho, g.magic_hp);
+      const int hi = rho - img * g.hp - p.pad, wi = c - p.pad;
+      if (prow < g.pr && img < p.n && hi >= 0 && hi < p.h && wi >= 0 && wi < p.w) {
+        voff[k] = ((img * p.h + hi) * p.w + wi) * xps + q * 16;    // the plan keeps x below 2 GiB
+      } else {
+        *(i32x4*)(patA + pos16 * 16) = i32x4{0, 0, 0, 0};
+        *(i32x4*)(patB + pos16 * 16) = i32x4{0, 0, 0, 0};
+      }
+      if (__ballot(voff[k] >= 0) != 0ull) smask |= 1u << k;
+    }
+  }
+  smask = __builtin_amdgcn_readfirstlane(smask);
+
+  // x at the first channel of super-stage sg
+  auto x_src = [&](int sg) __attribute__((always_inline)) {
+    const int ph = sg >= S0 ? 1 : 0;
+    const int ss = ph ? sg - S0 : sg;
+    return xbytes + (long long)((ph ? p.c_base : 0) + ss * CPS * g.ch) * eb;
+  };
+  {
+    const char* xs0 = x_src(0);
+#pragma unroll
+    for (int k = 0; k < KPW; ++k)
+      if (((smask >> k) & 1u) && voff[k] >= 0 && !(CG_KNOB & 128))
+        lds_direct16(xs0 + voff[k], patA + (wave + kWv * k) * 1024);
+  }
+
+  // ---- this lane's base-path pixels ------------------------------------------------------------
+  int pix[NF];
+  bool pval[NF];
+  int pa[NF][3];        // patch byte offsets of the three tap columns, kernel row 0
+#pragma unroll
+  for (int fp = 0; fp < NF; ++fp) {
+    pix[fp] = (wave * NF + fp) * 32 + lj;
+    pval[fp] = pix[fp] < bmv;
+    const int i = pval[fp] ? pix[fp] : 0;           // fragments past the tile's end read pixel 0 and are dropped
+    const int lr = fdiv3(i, g.magic_wo), wo_ = i - lr * p.wo;
+    const int R = R0 + lr;
+    const int img = fdiv3(R, g.magic_ho), hq = R - img * p.ho;
+    const int slot = ((img * g.hp + hq * p.stride - rho0) << g.logp) + wo_ * p.stride;
+    if (lh == 0) pslot[pix[fp]] = slot;
+#pragma unroll
+    for (int c = 0; c < 3; ++c) pa[fp][c] = slot_addr<CPS>(slot + c, lh);
+  }
+  bmp[tid * 2] = 0u;
+  bmp[tid * 2 + 1] = 0u;
+  if (tid < 64) {
+    tlo[tid] = my_lo;
+    thi[tid] = my_hi;
+  }
+
+  acc16 accP[NF][2], accR[NF][2];
+#pragma unroll
+  for (int fp = 0; fp < NF; ++fp)
+#pragma unroll
+    for (int fc = 0; fc < 2; ++fc)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        accP[fp][fc][i] = 0;
+        accR[fp][fc][i] = 0;
+      }
+
+  unsigned dlane[NF];   // this lane's decisions of pixel fp: bit 16*fc + i = channel 32*fc + 16*lh + i
+#pragma unroll
+  for (int fp = 0; fp < NF; ++fp) dlane[fp] = 0u;
+  int pac[NF][3];       // patch offsets of this lane's compacted pixels
+#pragma unroll
+  for (int fp = 0; fp < NF; ++fp)
+#pragma unroll
+    for (int c = 0; c < 3; ++c) pac[fp][c] = 0;
+  int nrl = 0;          // compacted fragments of this wavefront
+  int n_act = 0;        // fired pixels of the tile
+  const int wofs = lh * 1024 + lj * 16;   // lane's offset of its weight rows in a granule
+
+  CG_STAMP();
+  __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): the LDS-direct loads have landed
+  __syncthreads();
+  CG_STAMP();
+
+  // One weight granule (kernel row r of a super-stage) for NL pixel fragments: multiply it out of
+  // (pat, wg); meanwhile fetch the next granule's weights from ws into wgn (when ws is not null) and
+  // the patch load instructions k0 .. k0+KH-1 selected by pm of the next super-stage from xs into
+  // patn.  Over the granule the weight instructions go out first, then the patch instructions; the
+  // closing wait lets the latter stay in flight (they are needed when the super-stage ends).
+  auto granule = [&](auto nl_tag, acc16 (&acc)[NF][2], const int (&base)[NF][3], int r, const char* pat,
+                     char* patn, const char* wg, char* wgn, const char* ws, const char* xs, unsigned pm, int k0)
+                     __attribute__((always_inline)) {
+    constexpr int NL = decltype(nl_tag)::value;
+    int vsel[KH];
+#pragma unroll
+    for (int i = 0; i < KH; ++i) vsel[i] = (k0 == 0 || KH + i >= KPW) ? voff[i] : voff[KH + i < KPW ? KH + i : i];
+    auto part = [&](int t) __attribute__((always_inline)) {
+      constexpr int NU = WPW + KH;
+#pragma unroll
+      for (int u = (t * NU) / GK; u < ((t + 1) * NU) / GK; ++u) {
+        if (u < WPW) {
+          if (ws && !(CG_KNOB & 64)) issue_w(ws, wgn, u);
+        } else {
+          const int i = u - WPW;
+          if (((pm >> i) & 1u) && vsel[i] >= 0 && !(CG_KNOB & 32))
+            lds_direct16(xs + vsel[i], patn + (wave + kWv * (k0 + i)) * 1024);
+        }
+      }
+    };
+    int ar[NF][3];
+#pragma unroll
+    for (int fp = 0; fp < NF; ++fp)
+#pragma unroll
+      for (int c = 0; c < 3; ++c) ar[fp][c] = base[fp][c] + r * rowb;
+    mma_granule<Tr, NL, NF, CPS>(pat, wg, wofs, ar, acc, part, CG_KNOB);
+    CG_STAMP();
+    wait_vm(__popc(pm));
+  };
+  // the buffers of granule gi in super-stage sg: body(pat, patn, wg, wgn)
+  auto with_buffers = [&](int gi, int sg, auto&& body) __attribute__((always_inline)) {
+    const int po = (sg & 1) * PB, wo_ = (gi & 1) * GB;
+    body(pat2 + po, pat2 + (PB - po), wgt2 + wo_, wgt2 + (GB - wo_));
+  };
+  // prefetch state of granule (gi, sg, r)
+  auto prefetch_of = [&](int gi, int sg, int r, const char*& ws, const char*& xs, unsigned& pm, int& k0)
+                         __attribute__((always_inline)) {
+    ws = gi + 1 < G ? w_src(gi + 1) : nullptr;
+    k0 = r == 1 ? KH : 0;
+    pm = 0u;
+    xs = xbytes;
+    if (r < 2 && 3 * (sg + 1) < G) {
+      xs = x_src(sg + 1);
+      pm = (smask >> k0) & ((1u << KH) - 1u);
+      if (r == 1) pm &= (1u << (KPW - KH)) - 1u;
+    }
+  };
+
+  if (CG_KNOB & 512) return;
+  // ---- base path --------------------------------------------------------------------------------
+  int gi = 0;
+#pragma nounroll
+  for (int sg = 0; sg < S0; ++sg) {
+#pragma nounroll
+    for (int r = 0; r < 3; ++r, ++gi) {
+      const char *ws, *xs;
+      unsigned pm;
+      int k0;
+      prefetch_of(gi, sg, r, ws, xs, pm, k0);
+      with_buffers(gi, sg, [&](const char* pat, char* patn, const char* wg, char* wgn) __attribute__((always_inline)) {
+        granule(std::integral_constant<int, NF>{}, accP, pa, r, pat, patn, wg, wgn, ws, xs, pm, k0);
+      });
+      if (gi + 1 < 3 * S0 && !(CG_KNOB & 4)) __builtin_amdgcn_s_barrier();
+      CG_STAMP();
+    }
+  }
+
+  if (p.gated) {
+    // ---- gate -------------------------------------------------------------------------------
+    uint16_t* bmph = (uint16_t*)bmp;
+#pragma unroll
+    for (int fp = 0; fp < NF; ++fp) {
+      unsigned dl = 0u;
+#pragma unroll
+      for (int fc = 0; fc < 2; ++fc) {
+#pragma unroll
+        for (int q4 = 0; q4 < 4; ++q4) {
+          const int c0 = 32 * fc + 16 * lh + 4 * q4;
+          const i32x4 lo4 = *(const i32x4*)(tlo + c0);
+          const i32x4 hi4 = *(const i32x4*)(thi + c0);
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            const acc_t v = accP[fp][fc][4 * q4 + e];
+            bool f;
+            if constexpr (Base::kDtype == CG_I8)
+              f = Base::fires(v, lo4[e], hi4[e]);
+            else
+              f = Base::fires(v, __int_as_float(lo4[e]), __int_as_float(hi4[e]));
+            dl |= (f ? 1u : 0u) << (16 * fc + 4 * q4 + e);
+          }
+        }
+      }
+      if (!pval[fp]) dl = 0u;
+      dlane[fp] = dl;
+      bmph[pix[fp] * 4 + lh] = (uint16_t)(dl & 0xffffu);
+      bmph[pix[fp] * 4 + 2 + lh] = (uint16_t)(dl >> 16);
+    }
+    __syncthreads();
+
+    // ---- decision words out; compaction: every wavefront scans all pixels, wavefront c places
+    // pixels [64c, 64c+64)
+    if (p.bitmap && tid < bmv) {
+      const uint2 w2 = *(const uint2*)(bmp + tid * 2);
+      *(uint2*)(p.bitmap + (m0 + tid) * p.words + cbk * 2) = w2;
+    }
+    int my_prefix = 0;
+    unsigned long long my_bal = 0;
+#pragma unroll
+    for (int c = 0; c < BM / 64; ++c) {
+      const uint2 w2 = *(const uint2*)(bmp + (c * 64 + lane) * 2);
+      const unsigned long long b = __ballot((w2.x | w2.y) != 0u);
+      if (c == wave) {
+        my_prefix = n_act;
+        my_bal = b;
+      }
+      n_act += __popcll(b);
+    }
+    if ((my_bal >> lane) & 1ull) {
+      const int idx = my_prefix + __popcll(my_bal & ((1ull << lane) - 1ull));
+      clist[idx] = pslot[wave * 64 + lane];
+      rank[wave * 64 + lane] = (uint16_t)idx;
+    }
+    __syncthreads();
+
+    // compacted fragment c (32 pixels) goes to wavefront c % 4
+    const int nc = (n_act + 31) >> 5;
+    nrl = (nc > wave ? 1 : 0) + ((NF == 2 && nc > wave + kWv) ? 1 : 0);
+#pragma unroll
+    for (int k = 0; k < NF; ++k) {
+      const int c = (wave + kWv * k) * 32 + lj;
+      const int slot = clist[n_act == 0 ? 0 : (c < n_act ? c : 0)];
+#pragma unroll
+      for (int cc = 0; cc < 3; ++cc) pac[k][cc] = slot_addr<CPS>(slot + cc, lh);
+    }
+    CG_STAMP();
+
+    // ---- conditional path on the listed pixels -------------------------------------------------
+    if (n_act == 0) {
+      __builtin_amdgcn_s_waitcnt(0x0F70);   // nothing fired: drop the phase, drain what was prefetched
+      __syncthreads();
+    } else {
+#pragma nounroll
+      for (int sg = S0; sg < S; ++sg) {
+#pragma nounroll
+        for (int r = 0; r < 3; ++r, ++gi) {
+          const char *ws, *xs;
+          unsigned pm;
+          int k0;
+          prefetch_of(gi, sg, r, ws, xs, pm, k0);
+          with_buffers(gi, sg, [&](const char* pat, char* patn, const char* wg, char* wgn)
+                                   __attribute__((always_inline)) {
+            if (nrl == 2) {
+              if constexpr (NF == 2)
+                granule(std::integral_constant<int, 2>{}, accR, pac, r, pat, patn, wg, wgn, ws, xs, pm, k0);
+            } else if (nrl == 1) {
+              granule(std::integral_constant<int, 1>{}, accR, pac, r, pat, patn, wg, wgn, ws, xs, pm, k0);
+            } else {
+              granule(std::integral_constant<int, 0>{}, accR, pac, r, pat, patn, wg, wgn, ws, xs, pm, k0);
+            }
+          });
+          __builtin_amdgcn_s_barrier();
+        }
+      }
+    }
+  } else {
+    __syncthreads();
+  }
+
+  // ---- combine: R (compacted rows) goes through LDS, 64 rows at a time, to the lanes that hold P ----
+  if (p.gated && n_act > 0) {
+    const int npass = (n_act + 63) >> 6;
+    for (int q = 0; q < npass; ++q) {
+      // compacted fragments 2q and 2q+1 belong to wavefronts (2q)%4 and (2q)%4 + 1, their slot q/2
+      const int w0 = (2 * q) & 3, kk = q >> 1;
+      if ((wave == w0 || wave == w0 + 1) && nrl > kk) {
+        char* row = patA + ((wave - w0) * 32 + lj) * kRs + lh * 64;
+#pragma unroll
+        for (int k = 0; k < NF; ++k) {
+          if (k != kk) continue;
+#pragma unroll
+          for (int fc = 0; fc < 2; ++fc)
+#pragma unroll
+            for (int q4 = 0; q4 < 4; ++q4) {
+              i32x4 v;
+#pragma unroll
+              for (int e = 0; e < 4; ++e) {
+                const acc_t rv = accR[k][fc][4 * q4 + e];
+                v[e] = as_bits(rv);
+              }
+              *(i32x4*)(row + fc * 128 + q4 * 16) = v;
+            }
+        }
+      }
+      __syncthreads();
+#pragma unroll
+      for (int fp = 0; fp < NF; ++fp) {
+        if (dlane[fp]) {
+          const int r = (int)rank[pix[fp]] - 64 * q;
+          if (r >= 0 && r < 64) {
+            const char* row = patA + r * kRs + lh * 64;
+#pragma unroll
+            for (int fc = 0; fc < 2; ++fc)
+#pragma unroll
+              for (int q4 = 0; q4 < 4; ++q4) {
+                const i32x4 v = *(const i32x4*)(row + fc * 128 + q4 * 16);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                  const bool on = (dlane[fp] >> (16 * fc + 4 * q4 + e)) & 1u;
+                  acc_t rv;
+                  from_bits(v[e], rv);
+                  accP[fp][fc][4 * q4 + e] += on ? rv : (acc_t)0;
+                }
+              }
+          }
+        }
+      }
+      __syncthreads();
+    }
+  }
+  CG_STAMP();
+
+  if (CG_KNOB & 1024) return;
+  // ---- output function on 16 consecutive channels per accumulator ---------------------------------
+  const int ob = p.out_dtype == CG_BF16 ? 2 : p.out_dtype == CG_I8 ? 1 : 4;
+  if (ob == 4) {
+    // 4-byte outputs: a lane's 16 channels are 64 contiguous bytes; stored directly
+#pragma unroll
+    for (int fp = 0; fp < NF; ++fp) {
+      if (!pval[fp]) continue;
+#pragma unroll
+      for (int fc = 0; fc < 2; ++fc) {
+        const int co0 = cbk * kBn + 32 * fc + 16 * lh;
+        const long long o = (m0 + pix[fp]) * p.c_out + co0;
+        i32x4 v[4];
+#pragma unroll
+        for (int q4 = 0; q4 < 4; ++q4)
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            const acc_t sv = accP[fp][fc][4 * q4 + e];
+            v[q4][e] = as_bits(sv);
+          }
+        const unsigned d16 = (dlane[fp] >> (16 * fc)) & 0xffffu;
+        finish_store8<Base>(p, v[0], v[1], d16 & 0xffu, co0, o);
+        finish_store8<Base>(p, v[2], v[3], d16 >> 8, co0 + 8, o + 8);
+      }
+    }
+  } else {
+    // 2- and 1-byte outputs: the 64 channels of a pixel form one row of an LDS tile (fragment fp of
+    // every wavefront: 128 rows), which leaves as whole rows
+    const int rb = kBn * ob;            // bytes per pixel row: 128 or 64
+    const int rs = rb + 16;             // skewed row stride in LDS
+    const bool lean = Base::kDtype != CG_I8 && p.out_dtype == CG_BF16 &&
+                      !(p.epilogue & (CG_EPI_AFFINE | CG_EPI_RESIDUAL));
+    const float relu_lo = (p.epilogue & CG_EPI_RELU) ? 0.0f : -__builtin_inff();
+#pragma unroll
+    for (int fp = 0; fp < NF; ++fp) {
+      char* tileY = fp == 0 ? patB : patA;
+      {
+        char* row = tileY + (wave * 32 + lj) * rs;
+#pragma unroll
+        for (int fc = 0; fc < 2; ++fc) {
+          const int cl = 32 * fc + 16 * lh;          // first of this lane's 16 channels in the block
+          const int co0 = cbk * kBn + cl;
+          const long long o = (m0 + pix[fp]) * p.c_out + co0;
+          i32x4 v[4];
+#pragma unroll
+          for (int q4 = 0; q4 < 4; ++q4)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+              const acc_t sv = accP[fp][fc][4 * q4 + e];
+              v[q4][e] = as_bits(sv);
+            }
+          const unsigned d16 = (dlane[fp] >> (16 * fc)) & 0xffffu;
+          i32x4 o0 = {0, 0, 0, 0}, o1, o2 = {0, 0, 0, 0}, o3;
+          if (lean) {
+            // bf16 output, no scale/shift, no residual: ReLU (or nothing) and the conversion
+            if constexpr (Base::kDtype != CG_I8) {
+#pragma unroll
+              for (int e = 0; e < 4; ++e) {
+                o0[e] = (int)((uint32_t)float_to_bf16(fmaxf(__int_as_float(v[e >> 1][2 * (e & 1)]), relu_lo)) |
+                              ((uint32_t)float_to_bf16(fmaxf(__int_as_float(v[e >> 1][2 * (e & 1) + 1]), relu_lo)) << 16));
+                o2[e] = (int)((uint32_t)float_to_bf16(fmaxf(__int_as_float(v[2 + (e >> 1)][2 * (e & 1)]), relu_lo)) |
+                              ((uint32_t)float_to_bf16(fmaxf(__int_as_float(v[2 + (e >> 1)][2 * (e & 1) + 1]), relu_lo)) << 16));
+              }
+            }
+          } else if (pval[fp]) {
+            finish8<Base>(p, v[0], v[1], d16 & 0xffu, co0, o, o0, o1);
+            finish8<Base>(p, v[2], v[3], d16 >> 8, co0 + 8, o + 8, o2, o3);
+          }
+          if (ob == 2) {
+            *(i32x4*)(row + cl * 2) = o0;
+            *(i32x4*)(row + cl * 2 + 16) = o2;
+          } else {
+            *(i32x4*)(row + cl) = i32x4{o0[0], o0[1], o2[0], o2[1]};
+          }
+        }
+      }
+      CG_STAMP();
+      __syncthreads();
+      CG_STAMP();
+      // 16-byte pieces: piece id = row * (rb/16) + part
+      const int ppr = rb >> 4;            // pieces per row: 8 or 4
+      const int lpp = ppr == 8 ? 3 : 2;
+      for (int id = tid; id < 128 * ppr; id += kTh) {
+        const int row = id >> lpp, part = id & (ppr - 1);
+        const int px = ((row >> 5) * NF + fp) * 32 + (row & 31);     // tile pixel of this row
+        if (px < bmv && !(CG_KNOB & 8)) {
+          const i32x4 v = *(const i32x4*)(tileY + row * rs + part * 16);
+          *(i32x4*)((char*)p.y + ((m0 + px) * p.c_out + cbk * kBn) * ob + part * 16) = v;
+        }
+      }
+    }
+  }
+  CG_STAMP();
+#ifdef CG_PROFILE_KNOBS
+  if (stamp) {
+    long long* stamps = (long long*)p.counts + (blockIdx.x == 0 ? 1 : 33);
+    for (int i = 0; i < n_stamp; ++i) stamps[i] = stampbuf[i];
+  }
+#endif
+#undef CG_STAMP
+#undef CG_KNOB
+}
+
+// [c_out][9][c_phase] -> [column block][super-stage][kernel row r][K step k][chunk h][row][16 bytes]
+// with tap = 3r + k / (CPS/2) and chunk = CPS*sigma + 2*(k % (CPS/2)) + h; row rho of a 32-row
+// fragment holds channel 16*((rho/4)%2) + 4*(rho/8) + rho%4, which puts 16 consecutive channels in
+// one lane of the transposed product
+__global__ void pack_rows_kernel(const char* __restrict__ w, char* __restrict__ out, int c_phase, int eb, int ch,
+                                 int cps, int stages, long long total) {
+  const long long id = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (id >= total) return;
+  const int gk = 3 * cps / 2, pairs = cps / 2;
+  const int rho = (int)(id & 63);
+  long long r_ = id >> 6;
+  const int h = (int)(r_ & 1);
+  r_ >>= 1;
+  const int k = (int)(r_ % gk);
+  r_ /= gk;
+  const int kr = (int)(r_ % 3);
+  r_ /= 3;
+  const int ss = (int)(r_ % stages);
+  const int cb = (int)(r_ / stages);
+  const int tap = 3 * kr + k / pairs;
+  const int chunk = cps * ss + 2 * (k % pairs) + h;
+  const int fc = rho >> 5, rr = rho & 31;
+  const int co = cb * kBn + 32 * fc + 16 * ((rr >> 2) & 1) + 4 * (rr >> 3) + (rr & 3);
+  const char* src = w + (((long long)co * 9 + tap) * c_phase + chunk * ch) * eb;
+  *(i32x4*)(out + id * 16) = *(const i32x4*)src;
+}
+
+// per-(image, channel) fired counts and their total from the decision bitmap
+__global__ void bitmap_counts_kernel(const uint32_t* __restrict__ bitmap, int words, int hw, int c_out,
+                                     uint32_t* __restrict__ counts) {
+  __shared__ uint32_t cnt[32];
+  const int w = blockIdx.x % words, img = blockIdx.x / words;
+  if (threadIdx.x < 32) cnt[threadIdx.x] = 0u;
+  __syncthreads();
+  uint32_t mine[32];
+#pragma unroll
+  for (int b = 0; b < 32; ++b) mine[b] = 0u;
+  for (int px = threadIdx.x; px < hw; px += blockDim.x) {
+    const uint32_t v = bitmap[((long long)img * hw + px) * words + w];
+#pragma unroll
+    for (int b = 0; b < 32; ++b) mine[b] += (v >> b) & 1u;
+  }
+#pragma unroll
+  for (int b = 0; b < 32; ++b) {
+    uint32_t v = mine[b];
+#pragma unroll
+    for (int sft = 32; sft >= 1; sft >>= 1) v += (uint32_t)__shfl_xor((int)v, sft, 64);
+    if ((threadIdx.x & 63) == 0 && v) atomicAdd(&cnt[b], v);
+  }
+  __syncthreads();
+  if (threadIdx.x < 32) {
+    const int co = w * 32 + threadIdx.x;
+    const uint32_t v = cnt[threadIdx.x];
+    if (co < c_out) {
+      counts[2 + (long long)img * c_out + co] = v;
+      if (v) atomicAdd((unsigned long long*)counts, (unsigned long long)v);
+    }
+  }
+}
+
+template <typename Tr, int NF, int CPS, int PKB>
+hipError_t launch_rows_one(const Mfma3Plan& g, const Params& p, const void* w0, const void* w1, hipStream_t s) {
+  const long long rows = (long long)p.n * p.ho;
+  const long long tiles = (rows + g.tr - 1) / g.tr;
+  const long long blocks = ((tiles + 7) / 8) * 8 * g.n_cb;
+  if (blocks <= 0) return hipSuccess;
+  if (blocks > 0x7fffffffll) return hipErrorInvalidValue;
+  auto kern = gated_conv_rows_kernel<Tr, NF, CPS, PKB>;
+  hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(kTh), 0, s, p, g, (const char*)w0, (const char*)w1);
+  return hipGetLastError();
+}
+
+template <typename Tr, int NF>
+hipError_t launch_rows_nf(const Mfma3Plan& g, const Params& p, const void* w0, const void* w1, hipStream_t s) {
+  if (g.pkb == 24) {
+    if (g.cps == 4) return launch_rows_one<Tr, NF, 4, 24>(g, p, w0, w1, s);
+    return launch_rows_one<Tr, NF, 2, 24>(g, p, w0, w1, s);
+  }
+  if (g.cps == 4) return launch_rows_one<Tr, NF, 4, 48>(g, p, w0, w1, s);
+  return launch_rows_one<Tr, NF, 2, 48>(g, p, w0, w1, s);
+}
+
+template <typename Tr>
+hipError_t launch_rows_dtype(const Mfma3Plan& g, const Params& p, const void* w0, const void* w1, hipStream_t s) {
+  if (g.nf == 2) return launch_rows_nf<Tr, 2>(g, p, w0, w1, s);
+  return launch_rows_nf<Tr, 1>(g, p, w0, w1, s);
+}
+
+unsigned magic_of3(int d) { return (unsigned)(((1ull << 32) + (unsigned)d - 1) / (unsigned)d); }
+
+}  // namespace
+
+Mfma3Plan mfma3_plan(const cg_conv_desc& d) {
+  Mfma3Plan g{};
+  g.ok = 0;
+  if (d.in_dtype != CG_BF16 && d.in_dtype != CG_I8) return g;
+  if (d.kh != 3 || d.kw != 3) return g;
+  if (d.stride < 1 || d.stride > 2 || d.pad > 1) return g;
+  g.elem_bytes = d.in_dtype == CG_BF16 ? 2 : 1;
+  g.ch = 16 / g.elem_bytes;
+  const int c_cond = d.c_in - d.c_base;
+  const long long xps = d.x_pixel_stride ? d.x_pixel_stride : d.c_in;
+  if (xps % g.ch) return g;
+  if (d.c_base % (4 * g.ch) == 0 && c_cond % (4 * g.ch) == 0)
+    g.cps = 4;
+  else if (d.c_base % (2 * g.ch) == 0 && c_cond % (2 * g.ch) == 0)
+    g.cps = 2;
+  else
+    return g;
+  const char* env_cps = getenv("CG_MFMA3_CPS");
+  if (env_cps && atoi(env_cps) == 2) g.cps = 2;
+  if (d.c_out % kBn) return g;
+  const int ho = (d.h + 2 * d.pad - 3) / d.stride + 1, wo = (d.w + 2 * d.pad - 3) / d.stride + 1;
+  // 32-bit byte offsets and 16-bit row numbers inside the kernel
+  if ((long long)d.n_max * d.h * d.w * xps * g.elem_bytes >= (1ll << 31)) return g;
+  if ((long long)d.n_max * ho * wo >= (1ll << 30)) return g;
+  if ((long long)d.n_max * (d.h + 2 * d.pad) >= 65536 || (long long)d.n_max * ho >= 65536) return g;
+  g.n_cb = d.c_out / kBn;
+  g.hp = d.h + 2 * d.pad;
+  g.magic_hp = magic_of3(g.hp);
+  g.magic_ho = magic_of3(ho);
+  g.magic_wo = magic_of3(wo);
+  g.logp = 4;
+  while ((1 << g.logp) < d.w + d.pad) ++g.logp;
+  if ((1 << g.logp) == d.w + d.pad && d.pad) ++g.logp;   // keep a zero slot after the last column
+  if (g.logp > 8) return g;
+  const int P = 1 << g.logp;
+  const int sb = 16 * g.cps;
+  const long long rows = (long long)d.n_max * ho;
+  const char* env_nf = getenv("CG_MFMA3_NF");
+  const char* env_sl = getenv("CG_MFMA3_SLEEP");
+  g.phase_sleep = env_sl ? atoi(env_sl) : 0;
+  auto gcd = [](int a, int b) {
+    while (b) {
+      const int t = a % b;
+      a = b;
+      b = t;
+    }
+    return a;
+  };
+  // patch rows of a tile of t output rows, maximum over the tile starts that occur (multiples of t)
+  auto patch_rows = [&](int t) {
+    int pr = 0;
+    const int step = gcd(t, ho);
+    for (int r0 = 0; r0 < ho; r0 += step) {
+      const int r1 = r0 + t - 1;
+      const int rows_here = (r1 / ho) * g.hp + (r1 % ho) * d.stride - r0 * d.stride + 3;
+      if (rows_here > pr) pr = rows_here;
+    }
+    return pr;
+  };
+  // 24 KB patch buffers (two workgroups per CU) before 48 KB ones, the large tile before the small
+  // one; a candidate must keep three quarters of its pixel slots busy, and the large tile must
+  // still fill the 256 CUs
+  for (int pkb = 24; pkb <= 48; pkb += 24) {
+    for (int nf = 2; nf >= 1; --nf) {
+      if (env_nf && atoi(env_nf) != nf) continue;
+      const int bm = 128 * nf;
+      int tr = bm / wo;
+      if (tr < 1) continue;
+      if (tr > rows) tr = (int)rows;
+      int t = tr;
+      while (t >= 1 && (long long)patch_rows(t) * P * sb > pkb * 1024) --t;
+      if (t < 1 || 4 * t < 3 * tr) continue;
+      const long long tiles = (rows + t - 1) / t;
+      if (nf == 2 && !env_nf && tiles * g.n_cb < 256) continue;
+      g.nf = nf;
+      g.bm = bm;
+      g.tr = t;
+      g.pkb = pkb;
+      g.pr = patch_rows(t);
+      g.ni = (g.pr * P * g.cps + 63) / 64;
+      g.stages[0] = d.c_base / (g.cps * g.ch);
+      g.stages[1] = c_cond / (g.cps * g.ch);
+      const size_t gb = (size_t)(3 * g.cps / 2) * 2048;
+      g.wpk_base_bytes = (size_t)g.n_cb * g.stages[0] * 3 * gb;
+      g.wpk_cond_bytes = (size_t)g.n_cb * g.stages[1] * 3 * gb;
+      g.ok = 1;
+      return g;
+    }
+  }
+  return g;
+}
+
+hipError_t launch_mfma3_pack(const Mfma3Plan& g, const Params& p, void* wpk_base, void* wpk_cond, hipStream_t s) {
+  for (int ph = 0; ph < 2; ++ph) {
+    if (g.stages[ph] == 0) continue;
+    const long long total = (long long)g.n_cb * g.stages[ph] * 3 * (3 * g.cps / 2) * 2 * 64;
+    const unsigned blocks = (unsigned)((total + 255) / 256);
+    hipLaunchKernelGGL(pack_rows_kernel, dim3(blocks), dim3(256), 0, s, (const char*)(ph ? p.w_cond : p.w_base),
+                       (char*)(ph ? wpk_cond : wpk_base), ph ? p.c_cond : p.c_base, g.elem_bytes, g.ch, g.cps,
+                       g.stages[ph], total);
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+  }
+  return hipSuccess;
+}
+
+hipError_t launch_mfma3(const Mfma3Plan& g, const Params& p, const void* w0, const void* w1, hipStream_t s) {
+  if (p.in_dtype == CG_BF16) return launch_rows_dtype<Bf16Rows>(g, p, w0, w1, s);
+  return launch_rows_dtype<I8Rows>(g, p, w0, w1, s);
+}
+
+hipError_t launch_bitmap_counts(const Params& p, const uint32_t* bitmap, hipStream_t s) {
+  const long long blocks = (long long)p.n * p.words;
+  if (blocks <= 0) return hipSuccess;
+  hipLaunchKernelGGL(bitmap_counts_kernel, dim3((unsigned)blocks), dim3(256), 0, s, bitmap, p.words, p.ho * p.wo,
+                     p.c_out, p.counts);
+  return hipGetLastError();
+}
+
+}  // namespace cg

@@ -27,7 +27,7 @@ def test_imagenet_bf16_batch64(li):
     inp = W.make_inputs(shape, W.seed_for(3, li), kind="coherent", rho=0.30, round_bf16=True)
     gate = W.calibrate_gate(inp, 0.30, sample_images=8)
     rep = _say(P.run_float(inp, gate, in_dtype=B.CG_BF16, out_dtype=B.CG_BF16, name=shape.name + " N=64 bf16"))
-    assert rep.variant == B.CG_VARIANT_MFMA_COMPACT
+    assert rep.variant == B.CG_VARIANT_MFMA_ROWS
     assert 0.15 < rep.fired_frac < 0.5
     assert rep.flips < 1000
 
@@ -60,7 +60,7 @@ def test_imagenet_int8_bit_exact(li, n):
     q = W.quantize_int8(inp)
     thr = W.calibrate_gate_int8(q, 0.35, sample_images=8)
     rep = _say(P.run_int8(q, thr, name="%s N=%d int8" % (shape.name, n)))
-    assert rep.variant == B.CG_VARIANT_MFMA_COMPACT
+    assert rep.variant in (B.CG_VARIANT_MFMA_ROWS, B.CG_VARIANT_MFMA_COMPACT)
     rng = np.random.default_rng(li)
     rq = W.requant_params(q, rng)
     _say(P.run_int8(q, thr, out_i8=True, rq=rq, name="%s N=%d int8 requant" % (shape.name, n)))

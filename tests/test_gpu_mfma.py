@@ -15,12 +15,17 @@ def _say(rep):
     return rep
 
 
-VARIANTS = [B.CG_VARIANT_MFMA, B.CG_VARIANT_MFMA_COMPACT]
-VNAMES = ["blockskip", "compact"]
+VARIANTS = [B.CG_VARIANT_MFMA, B.CG_VARIANT_MFMA_COMPACT, B.CG_VARIANT_MFMA_ROWS]
+VNAMES = ["blockskip", "compact", "rows"]
 
 
-def _supported(shape, variant):
-    return not (variant == B.CG_VARIANT_MFMA_COMPACT and shape.k != 3)
+def _supported(shape, variant, int8=False):
+    if variant == B.CG_VARIANT_MFMA_COMPACT:
+        return shape.k == 3
+    if variant == B.CG_VARIANT_MFMA_ROWS:      # 3x3, K stages of two 16-byte channel chunks
+        two_chunks = 32 if int8 else 16
+        return shape.k == 3 and shape.c_base % two_chunks == 0 and (shape.c_in - shape.c_base) % two_chunks == 0
+    return True
 
 
 SMALL = [
@@ -48,7 +53,7 @@ SMALL = [
 @pytest.mark.parametrize("shape", SMALL, ids=[s.name for s in SMALL])
 def test_mfma_bf16_matches_oracle(shape, variant):
     if not _supported(shape, variant):
-        pytest.skip("1x1 layers run on the block-skipping kernel")
+        pytest.skip("shape outside this kernel family (1x1, or channel groups it cannot stage)")
     inp = W.make_inputs(shape, 1000 + shape.c_out + shape.h, kind="coherent", rho=0.3, round_bf16=True)
     gate = W.calibrate_gate(inp, 0.30, sample_images=None)
     rep = _say(P.run_float(inp, gate, in_dtype=B.CG_BF16, out_dtype=B.CG_F32, variant=variant,
@@ -60,8 +65,8 @@ def test_mfma_bf16_matches_oracle(shape, variant):
 @pytest.mark.parametrize("variant", VARIANTS, ids=VNAMES)
 @pytest.mark.parametrize("shape", SMALL, ids=[s.name for s in SMALL])
 def test_mfma_int8_bit_exact(shape, variant):
-    if not _supported(shape, variant):
-        pytest.skip("1x1 layers run on the block-skipping kernel")
+    if not _supported(shape, variant, int8=True):
+        pytest.skip("shape outside this kernel family (1x1, or channel groups it cannot stage)")
     if shape.c_base % 16:
         pytest.skip("int8 matrix-core path needs 16-channel groups")
     inp = W.make_inputs(shape, 2000 + shape.c_out + shape.h, kind="coherent", rho=0.35)
@@ -90,6 +95,8 @@ def test_mfma_delta_infinite(delta, frac, variant):
     gate.delta[:] = delta
     rep = _say(P.run_float(inp, gate, variant=variant, name="delta=%s" % delta))
     assert rep.fired_frac == frac and rep.flips == 0
+    if not _supported(shape, variant, int8=True):
+        return
     q = W.quantize_int8(W.make_inputs(shape, 42, kind="iid"))
     thr = np.full(64, np.iinfo(np.int32).min if delta < 0 else np.iinfo(np.int32).max, np.int32)
     rep = _say(P.run_int8(q, thr, variant=variant, name="int8 delta=%s" % delta))
@@ -145,7 +152,7 @@ def test_mfma_matches_naive_kernel_decisions():
     q = W.quantize_int8(W.make_inputs(shape, 81, kind="coherent", rho=0.35))
     thr = W.calibrate_gate_int8(q, 0.35, sample_images=None)
     outs = []
-    for variant in (B.CG_VARIANT_NAIVE, B.CG_VARIANT_MFMA, B.CG_VARIANT_MFMA_COMPACT):
+    for variant in (B.CG_VARIANT_NAIVE, B.CG_VARIANT_MFMA, B.CG_VARIANT_MFMA_COMPACT, B.CG_VARIANT_MFMA_ROWS):
         x = torch.from_numpy(q.x).cuda()
         layer = B.GatedConv(n_max=2, h=28, w=28, c_in=128, c_out=128, c_base=32,
                             w_base=torch.from_numpy(q.w_base).cuda(), w_cond=torch.from_numpy(q.w_cond).cuda(),
