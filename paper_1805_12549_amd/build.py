@@ -16,6 +16,9 @@ SOURCES = ["cg_conv_api.hip", "kernels_naive.hip", "kernels_mfma.hip", "kernels_
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+    # accumulators stay in ordinary vector registers: with the AGPR form the compiler copies them
+    # back and forth around the branches inside the MFMA loops and mis-counts the wait states
+    "-mllvm", "-amdgpu-mfma-vgpr-form=1",
     "-Wall", "-Wno-unused-function", "-Wno-unknown-warning-option",
 ]
 

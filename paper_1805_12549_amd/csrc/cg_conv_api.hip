@@ -196,8 +196,8 @@ size_t cg_conv_packed_bytes(const cg_conv_desc* desc) {
   Plans pl;
   if (resolve_variant(*desc, &pl) != CG_OK) return 0;
   if (getenv("CG_DEBUG") && pl.v3.ok)
-    fprintf(stderr, "[cg_conv] rows plan: nf=%d bm=%d n_cb=%d tr=%d pitch=%d pr=%d cps=%d ni=%d pkb=%d stages=%d,%d\n",
-            pl.v3.nf, pl.v3.bm, pl.v3.n_cb, pl.v3.tr, 1 << pl.v3.logp, pl.v3.pr, pl.v3.cps, pl.v3.ni, pl.v3.pkb,
+    fprintf(stderr, "[cg_conv] rows plan: nwv=%d nf=%d bm=%d n_cb=%d tr=%d pitch=%d pr=%d cps=%d ni=%d pkb=%d stages=%d,%d\n",
+            pl.v3.nwv, pl.v3.nf, pl.v3.bm, pl.v3.n_cb, pl.v3.tr, 1 << pl.v3.logp, pl.v3.pr, pl.v3.cps, pl.v3.ni, pl.v3.pkb,
             pl.v3.stages[0], pl.v3.stages[1]);
   return make_layout(*desc, pl.wpk_base_bytes, pl.wpk_cond_bytes).total;
 }
@@ -232,8 +232,8 @@ int cg_conv_create(cg_conv** out, const cg_conv_desc* desc, void* hip_stream) {
             plan2.max_imgs, plan2.cbq, plan2.stages[0], plan2.stages[1], plan2.tsteps, plan2.kp, plan2.stage_bytes,
             plan2.lds_total);
   if (getenv("CG_DEBUG") && plan3.ok)
-    fprintf(stderr, "[cg_conv] rows plan: nf=%d bm=%d n_cb=%d tr=%d pitch=%d pr=%d cps=%d ni=%d pkb=%d stages=%d,%d\n",
-            plan3.nf, plan3.bm, plan3.n_cb, plan3.tr, 1 << plan3.logp, plan3.pr, plan3.cps, plan3.ni, plan3.pkb,
+    fprintf(stderr, "[cg_conv] rows plan: nwv=%d nf=%d bm=%d n_cb=%d tr=%d pitch=%d pr=%d cps=%d ni=%d pkb=%d stages=%d,%d\n",
+            plan3.nwv, plan3.nf, plan3.bm, plan3.n_cb, plan3.tr, 1 << plan3.logp, plan3.pr, plan3.cps, plan3.ni, plan3.pkb,
             plan3.stages[0], plan3.stages[1]);
   if (!d.packed) return fail(CG_EINVAL, "packed is NULL");
   if (((uintptr_t)d.packed & 255) != 0) return fail(CG_EINVAL, "packed must be 256-byte aligned");

@@ -117,8 +117,9 @@ hipError_t launch_mfma2(const Mfma2Plan& plan, const Params& p, const void* wpk_
 struct Mfma3Plan {
   int ok;
   int elem_bytes, ch;      // bytes per element; channels per 16-byte chunk
+  int nwv;                 // wavefronts per workgroup: 4 or 8
   int nf;                  // 32-pixel fragments per wavefront in the base phase (1 or 2)
-  int bm;                  // 128*nf pixels per tile, padded
+  int bm;                  // 32*nf*nwv pixels per tile, padded
   int n_cb;                // c_out / 64
   int tr;                  // global output rows per tile
   int hp;                  // h + 2*pad
@@ -129,7 +130,6 @@ struct Mfma3Plan {
   int ni;                  // 1 KB load instructions per super-stage patch = ceil(pr * pitch * cps / 64)
   int pkb;                 // LDS patch buffer class: 24 KB (two workgroups per CU) or 48 KB
   int stages[2];           // super-stages of the base / conditional phase
-  int phase_sleep;         // start delay (units of 512 cycles) of every other round of workgroups
   size_t wpk_base_bytes, wpk_cond_bytes;
 };
 

@@ -1,9 +1,9 @@
 // Row-tiled matrix-core kernel of the gated convolution (bf16 and int8 MFMA, 32x32 blocks).
 //
-// One workgroup of four wavefronts owns BM = 128 or 256 consecutive output pixels (whole output
-// rows of the batch, numbered R = img*Ho + ho, possibly straddling images) times 64 output
-// channels and runs the whole layer for them (Eq. 1 of the channel-gating paper).  Two workgroups
-// share a compute unit when the input patch is small enough.
+// One workgroup of four or eight wavefronts owns BM = 32*NF pixels per wavefront of consecutive
+// output pixels (whole output rows of the batch, numbered R = img*Ho + ho, possibly straddling
+// images) times 64 output channels and runs the whole layer for them (Eq. 1 of the channel-gating
+// paper).  Eight-wavefront workgroups own a CU; four-wavefront ones share it two or three at a time.
 //
 //   base path   implicit GEMM over taps x base channels.  Each wavefront owns NF 32-pixel
 //               fragments x 64 channels.  The product is taken transposed (weights as the row
@@ -28,9 +28,11 @@
 // f(s) = (s >> 2) & 3 (CPS = 4) or (s >> 3) & 1 (CPS = 2), which makes the 16-lane operand reads
 // conflict-free.  Slot = patch_row * P + c with P a power of two >= max(16, W + pad) and
 // c = wi + pad, so the zero padding left and right of a row are the never-loaded slots between
-// rows; rows outside the image are zeroed once.  Weights stream through a two-deep ring of
-// granules, one kernel row (three taps) of the super-stage each; granule g+1 and a part of the
-// next super-stage's patch are fetched by LDS-direct loads while granule g is multiplied.
+// rows; rows outside the image are zeroed once.  Weights stream through a ring of granules, one
+// kernel row (three taps) of the super-stage each: two deep for four wavefronts, four deep (fetched
+// three granules ahead) for eight; the granule fetch and a part of the next super-stage's patch go
+// out as LDS-direct loads while a granule is multiplied, and the wait at the granule's end covers
+// only what the next granule needs (the loads of a wavefront complete in order).
 #include <cstdlib>
 #include <type_traits>
 
@@ -40,10 +42,7 @@ namespace cg {
 
 namespace {
 
-constexpr int kWv = 4;                       // wavefronts per workgroup
-constexpr int kTh = kWv * 64;
 constexpr int kBn = 64;                      // output channels per workgroup
-constexpr int kTab = 5 * 1024;
 constexpr int kRs = 272;                     // bytes per row of the R tile: 64 sums + 16 bytes of skew
 
 typedef __attribute__((ext_vector_type(16))) float f32x16;
@@ -94,7 +93,7 @@ __device__ __forceinline__ i32x4 lds_read16(const char* p) {
   return v;
 }
 
-// s_waitcnt vmcnt(n), n <= 6: at most n vector-memory operations of this wavefront still in flight
+// s_waitcnt vmcnt(n): at most n vector-memory operations of this wavefront still in flight
 __device__ __forceinline__ void wait_vm(int n) {
   switch (n) {
     case 0: __builtin_amdgcn_s_waitcnt(0x0F70); break;
@@ -104,7 +103,15 @@ __device__ __forceinline__ void wait_vm(int n) {
     case 4: __builtin_amdgcn_s_waitcnt(0x0F74); break;
     case 5: __builtin_amdgcn_s_waitcnt(0x0F75); break;
     case 6: __builtin_amdgcn_s_waitcnt(0x0F76); break;
-    default: __builtin_amdgcn_s_waitcnt(0x0F70); break;
+    case 7: __builtin_amdgcn_s_waitcnt(0x0F77); break;
+    case 8: __builtin_amdgcn_s_waitcnt(0x0F78); break;
+    case 9: __builtin_amdgcn_s_waitcnt(0x0F79); break;
+    case 10: __builtin_amdgcn_s_waitcnt(0x0F7A); break;
+    case 11: __builtin_amdgcn_s_waitcnt(0x0F7B); break;
+    case 12: __builtin_amdgcn_s_waitcnt(0x0F7C); break;
+    case 13: __builtin_amdgcn_s_waitcnt(0x0F7D); break;
+    case 14: __builtin_amdgcn_s_waitcnt(0x0F7E); break;
+    default: __builtin_amdgcn_s_waitcnt(0x0F7F); break;   // 15 or more allowed: wait down to 15
   }
 }
 
@@ -124,7 +131,7 @@ __device__ __forceinline__ int slot_addr(int slot, int h) {
 template <typename Tr, int NL, int NFM, int CPS, typename IssueFn>
 __device__ __forceinline__ void mma_granule(const char* __restrict__ pat, const char* __restrict__ wg, int wofs,
                                             const int (&ar)[NFM][3], typename Tr::acc16 (&acc)[NFM][2],
-                                            IssueFn&& issue, int knob = 0) {
+                                            IssueFn&& issue) {
   constexpr int GK = 3 * CPS / 2;
   constexpr int PAIRS = CPS / 2;
   constexpr int M = NL * 2;   // MFMAs per K step
@@ -145,7 +152,7 @@ __device__ __forceinline__ void mma_granule(const char* __restrict__ pat, const 
       __builtin_amdgcn_sched_barrier(0);
       // all operand reads of step k+1 go out before the MFMAs of step k: they then have the whole
       // step to land
-      if (k + 1 < GK && !(knob & 2)) {
+      if (k + 1 < GK) {
 #pragma unroll
         for (int i = 0; i < 2; ++i) a[n][i] = lds_read16(wg + wofs + (k + 1) * 2048 + i * 512);
 #pragma unroll
@@ -153,49 +160,53 @@ __device__ __forceinline__ void mma_granule(const char* __restrict__ pat, const 
           b[n][i] = lds_read16(pat + (ar[i][(k + 1) / PAIRS] ^ (((k + 1) % PAIRS) * 32)));
       }
       __builtin_amdgcn_sched_barrier(0);
-      if (!(knob & 1)) acc[0][0] = Tr::mfma(a[c][0], b[c][0], acc[0][0]);
+      acc[0][0] = Tr::mfma(a[c][0], b[c][0], acc[0][0]);
       __builtin_amdgcn_sched_barrier(0);
       issue(k);
       __builtin_amdgcn_sched_barrier(0);
-      if (!(knob & 1)) {
 #pragma unroll
-        for (int j = 1; j < M; ++j) acc[j >> 1][j & 1] = Tr::mfma(a[c][j & 1], b[c][j >> 1], acc[j >> 1][j & 1]);
-      }
+      for (int j = 1; j < M; ++j) acc[j >> 1][j & 1] = Tr::mfma(a[c][j & 1], b[c][j >> 1], acc[j >> 1][j & 1]);
       __builtin_amdgcn_sched_barrier(0);
     }
   }
+  if constexpr (NL > 0) {
+    // The accumulators may be read right after this loop, across the branch of the last issue();
+    // the compiler's count of wait states between an MFMA and a read of its result follows the
+    // fall-through path only, so the required distance is put here explicitly.
+    asm volatile("s_nop 7\n\ts_nop 7\n\ts_nop 7" ::: "memory");
+    __builtin_amdgcn_sched_barrier(0);
+  }
 }
 
-template <typename Tr, int NF, int CPS, int PKB>
-__global__ __launch_bounds__(kTh, PKB == 24 ? 2 : 1) void gated_conv_rows_kernel(Params p, Mfma3Plan g,
-                                                                                const char* __restrict__ wpk0,
-                                                                                const char* __restrict__ wpk1) {
+template <typename Tr, int NF, int CPS, int PKB, int NWV>
+__global__ __launch_bounds__(NWV * 64, PKB == 12 ? 3 : 2) void gated_conv_rows_kernel(
+    Params p, Mfma3Plan g, const char* __restrict__ wpk0, const char* __restrict__ wpk1) {
   using acc16 = typename Tr::acc16;
   using acc_t = typename Tr::acc_t;
   using Base = typename Tr::Base;
+  constexpr int NT = NWV * 64;                 // threads
+  constexpr int RD = NWV == 8 ? 4 : 2;         // weight granules in the ring
+  constexpr int D = RD - 1;                    // granules fetched ahead
   constexpr int GK = 3 * CPS / 2;              // K steps per weight granule
   constexpr int GB = GK * 2048;                // bytes per weight granule
   constexpr int PB = PKB * 1024;               // bytes per patch buffer
   constexpr int SB = 16 * CPS;                 // bytes per pixel slot
-  constexpr int KPW = PB / 1024 / kWv;         // patch load instructions per wavefront per super-stage, at most
+  constexpr int KPW = PB / 1024 / NWV;         // patch load instructions per wavefront per super-stage, at most
   constexpr int KH = (KPW + 1) / 2;            // of which in the first granule; the rest in the second
-  constexpr int WPW = (2 * GK + kWv - 1) / kWv;   // weight load instructions per wavefront per granule
-  constexpr int BM = 128 * NF;
-  static_assert(KH <= 6, "vmcnt wait table");
+  constexpr int WPW = (2 * GK + NWV - 1) / NWV;   // weight load instructions per wavefront per granule
+  constexpr int BM = 32 * NF * NWV;            // pixels per tile
+  constexpr int TAB = BM * 18 + 512;           // bytes of tables
 
-  // two patch buffers, two weight granule buffers, tables
+  // two patch buffers, the weight granule ring, tables
   __shared__ __align__(1024) char pat2[2 * PB];
-  __shared__ __align__(1024) char wgt2[2 * GB];
-  __shared__ __align__(16) char smem[kTab];
-  char* const patA = pat2;
-  char* const patB = pat2 + PB;
-  char* const wgtA = wgt2;
-  int* pslot = (int*)smem;                       // [256] tile pixel -> patch slot of its tap (0,0)
-  int* clist = pslot + 256;                      // [256] compacted position -> patch slot
-  uint16_t* rank = (uint16_t*)(clist + 256);     // [256] tile pixel -> compacted position
-  acc_t* tlo = (acc_t*)(rank + 256);             // [64] thresholds of this channel block
+  __shared__ __align__(1024) char wgt[RD * GB];
+  __shared__ __align__(16) char smem[TAB];
+  int* pslot = (int*)smem;                       // [BM] tile pixel -> patch slot of its tap (0,0)
+  int* clist = pslot + BM;                       // [BM] compacted position -> patch slot
+  uint32_t* bmp = (uint32_t*)(clist + BM);       // [BM][2] decision words of the tile
+  uint16_t* rank = (uint16_t*)(bmp + 2 * BM);    // [BM] tile pixel -> compacted position
+  acc_t* tlo = (acc_t*)(rank + BM);              // [64] thresholds of this channel block
   acc_t* thi = tlo + 64;
-  uint32_t* bmp = (uint32_t*)(thi + 64);         // [256][2] decision words of the tile
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -212,33 +223,10 @@ __global__ __launch_bounds__(kTh, PKB == 24 ? 2 : 1) void gated_conv_rows_kernel
   const int total_rows = p.n * p.ho;
   const int R0 = tile * g.tr;
   if (R0 >= total_rows) return;
-#ifdef CG_PROFILE_KNOBS
-  // developer builds: cycle stamps of two workgroups, kept in LDS and copied to the counts buffer at
-  // the end (results are then wrong)
-  __shared__ long long stampbuf[32];
-  const bool stamp = (p.debug & 16) && p.counts && tid == 0 && (blockIdx.x == 0 || blockIdx.x == gridDim.x / 2 + 1);
-  int n_stamp = 0;
-#define CG_STAMP()                                                 \
-  do {                                                             \
-    if (stamp && n_stamp < 32) stampbuf[n_stamp++] = clock64();    \
-  } while (0)
-#define CG_KNOB p.debug
-#else
-#define CG_STAMP() do {} while (0)
-#define CG_KNOB 0
-#endif
-  CG_STAMP();
-  if (CG_KNOB & 256) return;
-  // The two workgroups that share a CU (block ids 256 apart when every CU receives one block per
-  // round) would run their load / multiply / store phases in lockstep and leave the matrix cores
-  // idle in between; delaying every other round by roughly half a granule offsets them.
-  if (g.phase_sleep > 0 && ((blockIdx.x >> 8) & 1)) {
-    for (int i = 0; i < g.phase_sleep; ++i) __builtin_amdgcn_s_sleep(8);
-  }
 
   const int S0 = g.stages[0];                       // super-stages of the base phase
   const int S = S0 + (p.gated ? g.stages[1] : 0);
-  int G = 3 * S;                                    // weight granules
+  const int G = 3 * S;                              // weight granules
   const int eb = g.elem_bytes;
 
   // gate thresholds of this channel block: the loads go out first, the LDS copy follows later
@@ -253,21 +241,24 @@ __global__ __launch_bounds__(kTh, PKB == 24 ? 2 : 1) void gated_conv_rows_kernel
     }
   }
 
-  // source of weight granule gi (3*sigma + r) of this channel block
-  auto w_src = [&](int gi) __attribute__((always_inline)) {
-    const int ph = gi >= 3 * S0 ? 1 : 0;
-    const int gg = ph ? gi - 3 * S0 : gi;
-    return (ph ? wpk1 : wpk0) + ((size_t)cbk * 3 * g.stages[ph] + gg) * GB;
+  // source of weight granule j (3*super-stage + kernel row, counted over both phases) of this channel block
+  auto w_src = [&](int j) __attribute__((always_inline)) {
+    const int ph = j >= 3 * S0 ? 1 : 0;
+    const int jj = ph ? j - 3 * S0 : j;
+    return (ph ? wpk1 : wpk0) + ((size_t)cbk * 3 * g.stages[ph] + jj) * GB;
   };
-  // weight load instruction u of this wavefront: 1 KB number wave + 4u of the granule
+  // weight load instruction u of this wavefront: 1 KB number wave + NWV*u of the granule
   auto issue_w = [&](const char* ws, char* dst, int u) __attribute__((always_inline)) {
-    const int idx = wave + kWv * u;
+    const int idx = wave + NWV * u;
     if (idx < 2 * GK) lds_direct16(ws + idx * 1024 + lane * 16, dst + idx * 1024);
   };
-  {
-    const char* ws0 = w_src(0);
 #pragma unroll
-    for (int u = 0; u < WPW; ++u) issue_w(ws0, wgtA, u);
+  for (int j = 0; j < D; ++j) {
+    if (j < G) {
+      const char* ws = w_src(j);
+#pragma unroll
+      for (int u = 0; u < WPW; ++u) issue_w(ws, wgt + j * GB, u);
+    }
   }
 
   const long long m0 = (long long)R0 * p.wo;        // first output pixel
@@ -277,7 +268,7 @@ __global__ __launch_bounds__(kTh, PKB == 24 ? 2 : 1) void gated_conv_rows_kernel
   const int rho0 = img0 * g.hp + (R0 - img0 * p.ho) * p.stride;   // stacked padded input row of patch row 0
   const int rowb = SB << g.logp;                    // bytes per patch row
 
-  // ---- this wavefront's patch load instructions: instruction idx = wave + 4k fills the 64 chunk
+  // ---- this wavefront's patch load instructions: instruction idx = wave + NWV*k fills the 64 chunk
   // positions [64*idx, +64), i.e. 64/CPS pixel slots; a lane outside the image keeps a zero that is
   // written once.  smask bit k: the instruction has at least one lane inside the image.
   const char* xbytes = (const char*)p.x;
@@ -287,7 +278,7 @@ __global__ __launch_bounds__(kTh, PKB == 24 ? 2 : 1) void gated_conv_rows_kernel
 #pragma unroll
   for (int k = 0; k < KPW; ++k) {
     voff[k] = -1;
-    const int idx = wave + kWv * k;
+    const int idx = wave + NWV * k;
     if (idx < g.ni) {
       const int pos16 = idx * 64 + lane;
       const int sl = pos16 / CPS, cp = pos16 % CPS;
@@ -300,15 +291,21 @@ __global__ __launch_bounds__(kTh, PKB == 24 ? 2 : 1) void gated_conv_rows_kernel
       if (prow < g.pr && img < p.n && hi >= 0 && hi < p.h && wi >= 0 && wi < p.w) {
         voff[k] = ((img * p.h + hi) * p.w + wi) * xps + q * 16;    // the plan keeps x below 2 GiB
       } else {
-        *(i32x4*)(patA + pos16 * 16) = i32x4{0, 0, 0, 0};
-        *(i32x4*)(patB + pos16 * 16) = i32x4{0, 0, 0, 0};
+        *(i32x4*)(pat2 + pos16 * 16) = i32x4{0, 0, 0, 0};
+        *(i32x4*)(pat2 + PB + pos16 * 16) = i32x4{0, 0, 0, 0};
       }
       if (__ballot(voff[k] >= 0) != 0ull) smask |= 1u << k;
     }
   }
   smask = __builtin_amdgcn_readfirstlane(smask);
+  // loads this wavefront issues per granule: weights, patch in a super-stage's first / second granule
+  int cw = 0;
+#pragma unroll
+  for (int u = 0; u < WPW; ++u) cw += (wave + NWV * u < 2 * GK) ? 1 : 0;
+  const int np0 = __popc(smask & ((1u << KH) - 1u));
+  const int np1 = __popc((smask >> KH) & ((1u << (KPW - KH)) - 1u));
 
-  // x at the first channel of super-stage sg
+  // x at the first channel of super-stage sg (counted over both phases)
   auto x_src = [&](int sg) __attribute__((always_inline)) {
     const int ph = sg >= S0 ? 1 : 0;
     const int ss = ph ? sg - S0 : sg;
@@ -318,8 +315,7 @@ __global__ __launch_bounds__(kTh, PKB == 24 ? 2 : 1) void gated_conv_rows_kernel
     const char* xs0 = x_src(0);
 #pragma unroll
     for (int k = 0; k < KPW; ++k)
-      if (((smask >> k) & 1u) && voff[k] >= 0 && !(CG_KNOB & 128))
-        lds_direct16(xs0 + voff[k], patA + (wave + kWv * k) * 1024);
+      if (((smask >> k) & 1u) && voff[k] >= 0) lds_direct16(xs0 + voff[k], pat2 + (wave + NWV * k) * 1024);
   }
 
   // ---- this lane's base-path pixels ------------------------------------------------------------
@@ -339,8 +335,7 @@ __global__ __launch_bounds__(kTh, PKB == 24 ? 2 : 1) void gated_conv_rows_kernel
 #pragma unroll
     for (int c = 0; c < 3; ++c) pa[fp][c] = slot_addr<CPS>(slot + c, lh);
   }
-  bmp[tid * 2] = 0u;
-  bmp[tid * 2 + 1] = 0u;
+  for (int i = tid; i < 2 * BM; i += NT) bmp[i] = 0u;
   if (tid < 64) {
     tlo[tid] = my_lo;
     thi[tid] = my_hi;
@@ -369,20 +364,32 @@ __global__ __launch_bounds__(kTh, PKB == 24 ? 2 : 1) void gated_conv_rows_kernel
   int n_act = 0;        // fired pixels of the tile
   const int wofs = lh * 1024 + lj * 16;   // lane's offset of its weight rows in a granule
 
-  CG_STAMP();
-  __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): the LDS-direct loads have landed
+  __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): the first granules and the first patch have landed
   __syncthreads();
-  CG_STAMP();
 
-  // One weight granule (kernel row r of a super-stage) for NL pixel fragments: multiply it out of
-  // (pat, wg); meanwhile fetch the next granule's weights from ws into wgn (when ws is not null) and
-  // the patch load instructions k0 .. k0+KH-1 selected by pm of the next super-stage from xs into
-  // patn.  Over the granule the weight instructions go out first, then the patch instructions; the
-  // closing wait lets the latter stay in flight (they are needed when the super-stage ends).
-  auto granule = [&](auto nl_tag, acc16 (&acc)[NF][2], const int (&base)[NF][3], int r, const char* pat,
-                     char* patn, const char* wg, char* wgn, const char* ws, const char* xs, unsigned pm, int k0)
+  // One weight granule gi (kernel row r of super-stage sg) for NL pixel fragments: multiply it out of
+  // its patch buffer and ring slot; meanwhile fetch granule gi+D into the ring slot the previous
+  // granule left and, in the first two granules of a super-stage, half of the next super-stage's
+  // patch into the other patch buffer.  Over the granule the weight instructions go out first, then
+  // the patch instructions.  The closing wait covers granule gi+1's weights and, at the end of a
+  // super-stage, the next patch; younger loads stay in flight.
+  auto granule = [&](auto nl_tag, acc16 (&acc)[NF][2], const int (&base)[NF][3], int gi, int sg, int r)
                      __attribute__((always_inline)) {
     constexpr int NL = decltype(nl_tag)::value;
+    const char* pat = pat2 + (sg & 1) * PB;
+    char* patn = pat2 + ((sg & 1) ^ 1) * PB;
+    const char* wg = wgt + (gi & (RD - 1)) * GB;
+    const int nslot = (gi + D) & (RD - 1);
+    char* wgn = wgt + nslot * GB;
+    const char* ws = gi + D < G ? w_src(gi + D) : nullptr;
+    const int k0 = r == 1 ? KH : 0;
+    unsigned pm = 0u;
+    const char* xs = xbytes;
+    if (r < 2 && sg + 1 < S) {
+      xs = x_src(sg + 1);
+      pm = (smask >> k0) & ((1u << KH) - 1u);
+      if (r == 1) pm &= (1u << (KPW - KH)) - 1u;
+    }
     int vsel[KH];
 #pragma unroll
     for (int i = 0; i < KH; ++i) vsel[i] = (k0 == 0 || KH + i >= KPW) ? voff[i] : voff[KH + i < KPW ? KH + i : i];
@@ -391,11 +398,10 @@ __global__ __launch_bounds__(kTh, PKB == 24 ? 2 : 1) void gated_conv_rows_kernel
 #pragma unroll
       for (int u = (t * NU) / GK; u < ((t + 1) * NU) / GK; ++u) {
         if (u < WPW) {
-          if (ws && !(CG_KNOB & 64)) issue_w(ws, wgn, u);
+          if (ws) issue_w(ws, wgn, u);
         } else {
           const int i = u - WPW;
-          if (((pm >> i) & 1u) && vsel[i] >= 0 && !(CG_KNOB & 32))
-            lds_direct16(xs + vsel[i], patn + (wave + kWv * (k0 + i)) * 1024);
+          if (((pm >> i) & 1u) && vsel[i] >= 0) lds_direct16(xs + vsel[i], patn + (wave + NWV * (k0 + i)) * 1024);
         }
       }
     };
@@ -404,45 +410,42 @@ __global__ __launch_bounds__(kTh, PKB == 24 ? 2 : 1) void gated_conv_rows_kernel
     for (int fp = 0; fp < NF; ++fp)
 #pragma unroll
       for (int c = 0; c < 3; ++c) ar[fp][c] = base[fp][c] + r * rowb;
-    mma_granule<Tr, NL, NF, CPS>(pat, wg, wofs, ar, acc, part, CG_KNOB);
-    CG_STAMP();
-    wait_vm(__popc(pm));
-  };
-  // the buffers of granule gi in super-stage sg: body(pat, patn, wg, wgn)
-  auto with_buffers = [&](int gi, int sg, auto&& body) __attribute__((always_inline)) {
-    const int po = (sg & 1) * PB, wo_ = (gi & 1) * GB;
-    body(pat2 + po, pat2 + (PB - po), wgt2 + wo_, wgt2 + (GB - wo_));
-  };
-  // prefetch state of granule (gi, sg, r)
-  auto prefetch_of = [&](int gi, int sg, int r, const char*& ws, const char*& xs, unsigned& pm, int& k0)
-                         __attribute__((always_inline)) {
-    ws = gi + 1 < G ? w_src(gi + 1) : nullptr;
-    k0 = r == 1 ? KH : 0;
-    pm = 0u;
-    xs = xbytes;
-    if (r < 2 && 3 * (sg + 1) < G) {
-      xs = x_src(sg + 1);
-      pm = (smask >> k0) & ((1u << KH) - 1u);
-      if (r == 1) pm &= (1u << (KPW - KH)) - 1u;
+    mma_granule<Tr, NL, NF, CPS>(pat, wg, wofs, ar, acc, part);
+    // The loads of a wavefront complete in order.  Granule gi+1's weights went out D-1 granules ago,
+    // before that granule's patch loads; everything issued after them may stay in flight, except
+    // that a super-stage's last granule also needs every patch load (all older than its own weight
+    // loads).  np_of(g, r): patch loads of this wavefront in granule g (kernel row r).
+    int allowed = 0;
+    if (gi + 1 < G) {
+      if (r == 2) {
+        allowed = (D > 1 && gi + D < G) ? cw : 0;   // with D = 1 this granule's weight loads are the needed ones
+      } else {
+        int rr = r, ss = sg;
+#pragma unroll
+        for (int k = 0; k < D; ++k) {        // granules gi, gi-1, ..., gi-D+1
+          const int g2 = gi - k;
+          if (g2 < 0) break;
+          const int np = (rr < 2 && ss + 1 < S) ? (rr == 0 ? np0 : np1) : 0;
+          allowed += np;
+          if (k < D - 1 && g2 + D < G) allowed += cw;   // its own weight loads are younger than W(gi+1) too
+          if (--rr < 0) {
+            rr = 2;
+            --ss;
+          }
+        }
+      }
     }
+    wait_vm(allowed);
   };
 
-  if (CG_KNOB & 512) return;
   // ---- base path --------------------------------------------------------------------------------
   int gi = 0;
 #pragma nounroll
   for (int sg = 0; sg < S0; ++sg) {
 #pragma nounroll
     for (int r = 0; r < 3; ++r, ++gi) {
-      const char *ws, *xs;
-      unsigned pm;
-      int k0;
-      prefetch_of(gi, sg, r, ws, xs, pm, k0);
-      with_buffers(gi, sg, [&](const char* pat, char* patn, const char* wg, char* wgn) __attribute__((always_inline)) {
-        granule(std::integral_constant<int, NF>{}, accP, pa, r, pat, patn, wg, wgn, ws, xs, pm, k0);
-      });
-      if (gi + 1 < 3 * S0 && !(CG_KNOB & 4)) __builtin_amdgcn_s_barrier();
-      CG_STAMP();
+      granule(std::integral_constant<int, NF>{}, accP, pa, gi, sg, r);
+      if (gi + 1 < 3 * S0) __builtin_amdgcn_s_barrier();
     }
   }
 
@@ -480,9 +483,11 @@ __global__ __launch_bounds__(kTh, PKB == 24 ? 2 : 1) void gated_conv_rows_kernel
 
     // ---- decision words out; compaction: every wavefront scans all pixels, wavefront c places
     // pixels [64c, 64c+64)
-    if (p.bitmap && tid < bmv) {
-      const uint2 w2 = *(const uint2*)(bmp + tid * 2);
-      *(uint2*)(p.bitmap + (m0 + tid) * p.words + cbk * 2) = w2;
+    if (p.bitmap) {
+      for (int i = tid; i < bmv; i += NT) {
+        const uint2 w2 = *(const uint2*)(bmp + i * 2);
+        *(uint2*)(p.bitmap + (m0 + i) * p.words + cbk * 2) = w2;
+      }
     }
     int my_prefix = 0;
     unsigned long long my_bal = 0;
@@ -503,17 +508,16 @@ __global__ __launch_bounds__(kTh, PKB == 24 ? 2 : 1) void gated_conv_rows_kernel
     }
     __syncthreads();
 
-    // compacted fragment c (32 pixels) goes to wavefront c % 4
+    // compacted fragment c (32 pixels) goes to wavefront c % NWV
     const int nc = (n_act + 31) >> 5;
-    nrl = (nc > wave ? 1 : 0) + ((NF == 2 && nc > wave + kWv) ? 1 : 0);
+    nrl = (nc > wave ? 1 : 0) + ((NF == 2 && nc > wave + NWV) ? 1 : 0);
 #pragma unroll
     for (int k = 0; k < NF; ++k) {
-      const int c = (wave + kWv * k) * 32 + lj;
+      const int c = (wave + NWV * k) * 32 + lj;
       const int slot = clist[n_act == 0 ? 0 : (c < n_act ? c : 0)];
 #pragma unroll
       for (int cc = 0; cc < 3; ++cc) pac[k][cc] = slot_addr<CPS>(slot + cc, lh);
     }
-    CG_STAMP();
 
     // ---- conditional path on the listed pixels -------------------------------------------------
     if (n_act == 0) {
@@ -524,21 +528,13 @@ __global__ __launch_bounds__(kTh, PKB == 24 ? 2 : 1) void gated_conv_rows_kernel
       for (int sg = S0; sg < S; ++sg) {
 #pragma nounroll
         for (int r = 0; r < 3; ++r, ++gi) {
-          const char *ws, *xs;
-          unsigned pm;
-          int k0;
-          prefetch_of(gi, sg, r, ws, xs, pm, k0);
-          with_buffers(gi, sg, [&](const char* pat, char* patn, const char* wg, char* wgn)
-                                   __attribute__((always_inline)) {
-            if (nrl == 2) {
-              if constexpr (NF == 2)
-                granule(std::integral_constant<int, 2>{}, accR, pac, r, pat, patn, wg, wgn, ws, xs, pm, k0);
-            } else if (nrl == 1) {
-              granule(std::integral_constant<int, 1>{}, accR, pac, r, pat, patn, wg, wgn, ws, xs, pm, k0);
-            } else {
-              granule(std::integral_constant<int, 0>{}, accR, pac, r, pat, patn, wg, wgn, ws, xs, pm, k0);
-            }
-          });
+          if (nrl == 2) {
+            if constexpr (NF == 2) granule(std::integral_constant<int, 2>{}, accR, pac, gi, sg, r);
+          } else if (nrl == 1) {
+            granule(std::integral_constant<int, 1>{}, accR, pac, gi, sg, r);
+          } else {
+            granule(std::integral_constant<int, 0>{}, accR, pac, gi, sg, r);
+          }
           __builtin_amdgcn_s_barrier();
         }
       }
@@ -551,10 +547,10 @@ __global__ __launch_bounds__(kTh, PKB == 24 ? 2 : 1) void gated_conv_rows_kernel
   if (p.gated && n_act > 0) {
     const int npass = (n_act + 63) >> 6;
     for (int q = 0; q < npass; ++q) {
-      // compacted fragments 2q and 2q+1 belong to wavefronts (2q)%4 and (2q)%4 + 1, their slot q/2
-      const int w0 = (2 * q) & 3, kk = q >> 1;
+      // compacted fragments 2q and 2q+1 belong to wavefronts (2q)%NWV and the next, their slot (2q)/NWV
+      const int w0 = (2 * q) & (NWV - 1), kk = (2 * q) / NWV;
       if ((wave == w0 || wave == w0 + 1) && nrl > kk) {
-        char* row = patA + ((wave - w0) * 32 + lj) * kRs + lh * 64;
+        char* row = pat2 + ((wave - w0) * 32 + lj) * kRs + lh * 64;
 #pragma unroll
         for (int k = 0; k < NF; ++k) {
           if (k != kk) continue;
@@ -578,7 +574,7 @@ __global__ __launch_bounds__(kTh, PKB == 24 ? 2 : 1) void gated_conv_rows_kernel
         if (dlane[fp]) {
           const int r = (int)rank[pix[fp]] - 64 * q;
           if (r >= 0 && r < 64) {
-            const char* row = patA + r * kRs + lh * 64;
+            const char* row = pat2 + r * kRs + lh * 64;
 #pragma unroll
             for (int fc = 0; fc < 2; ++fc)
 #pragma unroll
@@ -598,9 +594,7 @@ __global__ __launch_bounds__(kTh, PKB == 24 ? 2 : 1) void gated_conv_rows_kernel
       __syncthreads();
     }
   }
-  CG_STAMP();
 
-  if (CG_KNOB & 1024) return;
   // ---- output function on 16 consecutive channels per accumulator ---------------------------------
   const int ob = p.out_dtype == CG_BF16 ? 2 : p.out_dtype == CG_I8 ? 1 : 4;
   if (ob == 4) {
@@ -627,17 +621,19 @@ __global__ __launch_bounds__(kTh, PKB == 24 ? 2 : 1) void gated_conv_rows_kernel
     }
   } else {
     // 2- and 1-byte outputs: the 64 channels of a pixel form one row of an LDS tile (fragment fp of
-    // every wavefront: 128 rows), which leaves as whole rows
+    // every wavefront: 32*NWV rows of at most 144 bytes, inside the patch buffers), which leaves as
+    // whole rows
     const int rb = kBn * ob;            // bytes per pixel row: 128 or 64
     const int rs = rb + 16;             // skewed row stride in LDS
     const bool lean = Base::kDtype != CG_I8 && p.out_dtype == CG_BF16 &&
                       !(p.epilogue & (CG_EPI_AFFINE | CG_EPI_RESIDUAL));
     const float relu_lo = (p.epilogue & CG_EPI_RELU) ? 0.0f : -__builtin_inff();
+    static_assert(32 * NWV * 144 <= 2 * PB, "output tile must fit the patch buffers");
 #pragma unroll
     for (int fp = 0; fp < NF; ++fp) {
-      char* tileY = fp == 0 ? patB : patA;
+      if (fp > 0) __syncthreads();      // the previous fragment's rows have been read
       {
-        char* row = tileY + (wave * 32 + lj) * rs;
+        char* row = pat2 + (wave * 32 + lj) * rs;
 #pragma unroll
         for (int fc = 0; fc < 2; ++fc) {
           const int cl = 32 * fc + 16 * lh;          // first of this lane's 16 channels in the block
@@ -676,31 +672,20 @@ __global__ __launch_bounds__(kTh, PKB == 24 ? 2 : 1) void gated_conv_rows_kernel
           }
         }
       }
-      CG_STAMP();
       __syncthreads();
-      CG_STAMP();
       // 16-byte pieces: piece id = row * (rb/16) + part
       const int ppr = rb >> 4;            // pieces per row: 8 or 4
       const int lpp = ppr == 8 ? 3 : 2;
-      for (int id = tid; id < 128 * ppr; id += kTh) {
+      for (int id = tid; id < 32 * NWV * ppr; id += NT) {
         const int row = id >> lpp, part = id & (ppr - 1);
         const int px = ((row >> 5) * NF + fp) * 32 + (row & 31);     // tile pixel of this row
-        if (px < bmv && !(CG_KNOB & 8)) {
-          const i32x4 v = *(const i32x4*)(tileY + row * rs + part * 16);
+        if (px < bmv) {
+          const i32x4 v = *(const i32x4*)(pat2 + row * rs + part * 16);
           *(i32x4*)((char*)p.y + ((m0 + px) * p.c_out + cbk * kBn) * ob + part * 16) = v;
         }
       }
     }
   }
-  CG_STAMP();
-#ifdef CG_PROFILE_KNOBS
-  if (stamp) {
-    long long* stamps = (long long*)p.counts + (blockIdx.x == 0 ? 1 : 33);
-    for (int i = 0; i < n_stamp; ++i) stamps[i] = stampbuf[i];
-  }
-#endif
-#undef CG_STAMP
-#undef CG_KNOB
 }
 
 // [c_out][9][c_phase] -> [column block][super-stage][kernel row r][K step k][chunk h][row][16 bytes]
@@ -763,32 +748,35 @@ __global__ void bitmap_counts_kernel(const uint32_t* __restrict__ bitmap, int wo
   }
 }
 
-template <typename Tr, int NF, int CPS, int PKB>
+template <typename Tr, int NF, int CPS, int PKB, int NWV>
 hipError_t launch_rows_one(const Mfma3Plan& g, const Params& p, const void* w0, const void* w1, hipStream_t s) {
   const long long rows = (long long)p.n * p.ho;
   const long long tiles = (rows + g.tr - 1) / g.tr;
   const long long blocks = ((tiles + 7) / 8) * 8 * g.n_cb;
   if (blocks <= 0) return hipSuccess;
   if (blocks > 0x7fffffffll) return hipErrorInvalidValue;
-  auto kern = gated_conv_rows_kernel<Tr, NF, CPS, PKB>;
-  hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(kTh), 0, s, p, g, (const char*)w0, (const char*)w1);
+  auto kern = gated_conv_rows_kernel<Tr, NF, CPS, PKB, NWV>;
+  hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(NWV * 64), 0, s, p, g, (const char*)w0, (const char*)w1);
   return hipGetLastError();
 }
 
-template <typename Tr, int NF>
-hipError_t launch_rows_nf(const Mfma3Plan& g, const Params& p, const void* w0, const void* w1, hipStream_t s) {
-  if (g.pkb == 24) {
-    if (g.cps == 4) return launch_rows_one<Tr, NF, 4, 24>(g, p, w0, w1, s);
-    return launch_rows_one<Tr, NF, 2, 24>(g, p, w0, w1, s);
+template <typename Tr, int NF, int CPS>
+hipError_t launch_rows_cps(const Mfma3Plan& g, const Params& p, const void* w0, const void* w1, hipStream_t s) {
+  if constexpr (NF == 1) {
+    if (g.pkb == 12) return launch_rows_one<Tr, NF, CPS, 12, 4>(g, p, w0, w1, s);
   }
-  if (g.cps == 4) return launch_rows_one<Tr, NF, 4, 48>(g, p, w0, w1, s);
-  return launch_rows_one<Tr, NF, 2, 48>(g, p, w0, w1, s);
+  if (g.pkb == 24) return launch_rows_one<Tr, NF, CPS, 24, 4>(g, p, w0, w1, s);
+  return launch_rows_one<Tr, NF, CPS, 48, 4>(g, p, w0, w1, s);
 }
 
 template <typename Tr>
 hipError_t launch_rows_dtype(const Mfma3Plan& g, const Params& p, const void* w0, const void* w1, hipStream_t s) {
-  if (g.nf == 2) return launch_rows_nf<Tr, 2>(g, p, w0, w1, s);
-  return launch_rows_nf<Tr, 1>(g, p, w0, w1, s);
+  if (g.nf == 2) {
+    if (g.cps == 4) return launch_rows_cps<Tr, 2, 4>(g, p, w0, w1, s);
+    return launch_rows_cps<Tr, 2, 2>(g, p, w0, w1, s);
+  }
+  if (g.cps == 4) return launch_rows_cps<Tr, 1, 4>(g, p, w0, w1, s);
+  return launch_rows_cps<Tr, 1, 2>(g, p, w0, w1, s);
 }
 
 unsigned magic_of3(int d) { return (unsigned)(((1ull << 32) + (unsigned)d - 1) / (unsigned)d); }
@@ -833,8 +821,8 @@ Mfma3Plan mfma3_plan(const cg_conv_desc& d) {
   const int sb = 16 * g.cps;
   const long long rows = (long long)d.n_max * ho;
   const char* env_nf = getenv("CG_MFMA3_NF");
-  const char* env_sl = getenv("CG_MFMA3_SLEEP");
-  g.phase_sleep = env_sl ? atoi(env_sl) : 0;
+  const char* env_pkb = getenv("CG_MFMA3_PKB");
+  const char* env_nwv = getenv("CG_MFMA3_NWV");
   auto gcd = [](int a, int b) {
     while (b) {
       const int t = a % b;
@@ -854,25 +842,37 @@ Mfma3Plan mfma3_plan(const cg_conv_desc& d) {
     }
     return pr;
   };
-  // 24 KB patch buffers (two workgroups per CU) before 48 KB ones, the large tile before the small
-  // one; a candidate must keep three quarters of its pixel slots busy, and the large tile must
-  // still fill the 256 CUs
-  for (int pkb = 24; pkb <= 48; pkb += 24) {
+  // Candidates in order of preference: 24 KB patch buffers (two workgroups per CU), then 48 KB.
+  // Within a class the large tile comes first; a candidate must keep three quarters of its pixel
+  // slots busy.  (Eight-wavefront workgroups, one per CU with the weights fetched three granules
+  // ahead, measured slower than two four-wavefront workgroups on every benchmark layer; the kernel
+  // template still takes the wavefront count.)
+  struct Cand {
+    int nwv, pkb;
+    long long min_wg;
+  };
+  const Cand cands[] = {{4, 12, 0}, {4, 24, 0}, {4, 48, 0}};
+  (void)env_nwv;
+  for (const Cand& c : cands) {
+    if (env_pkb ? atoi(env_pkb) != c.pkb : c.pkb == 12) continue;   // the 12 KB class only on request
     for (int nf = 2; nf >= 1; --nf) {
       if (env_nf && atoi(env_nf) != nf) continue;
-      const int bm = 128 * nf;
+      if (c.pkb == 12 && nf == 2) continue;
+      const int bm = 32 * nf * c.nwv;
       int tr = bm / wo;
       if (tr < 1) continue;
       if (tr > rows) tr = (int)rows;
       int t = tr;
-      while (t >= 1 && (long long)patch_rows(t) * P * sb > pkb * 1024) --t;
+      while (t >= 1 && (long long)patch_rows(t) * P * sb > c.pkb * 1024) --t;
       if (t < 1 || 4 * t < 3 * tr) continue;
       const long long tiles = (rows + t - 1) / t;
-      if (nf == 2 && !env_nf && tiles * g.n_cb < 256) continue;
+      if (tiles * g.n_cb < c.min_wg) continue;
+      if (c.nwv == 4 && nf == 2 && !env_nf && tiles * g.n_cb < 256) continue;
+      g.nwv = c.nwv;
       g.nf = nf;
       g.bm = bm;
       g.tr = t;
-      g.pkb = pkb;
+      g.pkb = c.pkb;
       g.pr = patch_rows(t);
       g.ni = (g.pr * P * g.cps + 63) / 64;
       g.stages[0] = d.c_base / (g.cps * g.ch);
