@@ -191,9 +191,9 @@ def main():
     t_kernel_us = sum(L["us_gated"] for L in layers)
     achieved = alg_flops / (t_kernel_us * 1e-6) / 1e12
     traffic = None     # measured HBM bytes per launch, from the committed counter summary
-    tfile = ROOT / "profiles" / "hbm_traffic_gated_conv_compact_kernel_imagenet_resnet18_bf16_n64.txt"
+    tfile = ROOT / "profiles" / "hbm_traffic_gated_conv_rows_kernel_imagenet_resnet18_bf16_n64.txt"
     if (tfile.exists() and args.batch == 64 and not args.layers and args.kind == "coherent"
-            and layers[0]["gated"].variant == B.CG_VARIANT_MFMA_COMPACT):
+            and layers[0]["gated"].variant == B.CG_VARIANT_MFMA_ROWS):
         m = re.search(r"^bytes_per_launch:\s*(\d+)", tfile.read_text(), re.M)
         traffic = int(m.group(1)) if m else None
     roofline = dict(bound="mfma", achieved=round(achieved, 2), peak=PEAK_BF16_TFLOPS, unit="TFLOP/s",
