@@ -49,7 +49,7 @@ class _Problem(C.Structure):
         ("c_out", C.c_int32), ("c_base", C.c_int32),
         ("kh", C.c_int32), ("kw", C.c_int32), ("stride", C.c_int32), ("pad", C.c_int32),
         ("is_int", C.c_int32), ("out_i8", C.c_int32), ("epilogue", C.c_uint32),
-        ("two_sided", C.c_int32),
+        ("two_sided", C.c_int32), ("groups", C.c_int32), ("shuffle", C.c_int32),
         ("x", _pd), ("w_base", _pd), ("w_cond", _pd),
         ("gate_mean", _pd), ("gate_var", _pd), ("delta", _pd), ("delta_hi", _pd),
         ("gate_eps", C.c_double),
@@ -93,9 +93,11 @@ def _ptr(a, ptype):
 
 def forward_float(x, w_base, w_cond, *, stride=1, pad=1, gate_mean=None, gate_var=None, delta=None,
                   delta_hi=None, gate_eps=0.0, scale0=None, shift0=None, scale1=None, shift1=None,
-                  residual=None, epilogue=RELU, want_partials=True):
+                  residual=None, epilogue=RELU, want_partials=True, groups=1, shuffle=False):
     """Float path.  x [N,H,W,C_in]; w_base [C_out,kh,kw,C_base]; w_cond [C_out,kh,kw,C_in-C_base]
-    (None or zero-width for a dense layer).  Every array is widened to float64 exactly."""
+    (None or zero-width for a dense layer).  Every array is widened to float64 exactly.
+    groups > 1: channel grouping (output group i uses input group i as base), optionally with the
+    output channels of y stored shuffled."""
     lib = _load()
     x = _as(x, np.float64)
     w_base = _as(w_base, np.float64)
@@ -135,6 +137,7 @@ def forward_float(x, w_base, w_cond, *, stride=1, pad=1, gate_mean=None, gate_va
     p.kh, p.kw, p.stride, p.pad = kh, kw, stride, pad
     p.is_int, p.out_i8, p.epilogue = 0, 0, epilogue
     p.two_sided = 1 if delta_hi is not None else 0
+    p.groups, p.shuffle = int(groups), int(bool(shuffle))
     p.gate_eps = gate_eps
     for name in ("x", "w_base", "w_cond", "gate_mean", "gate_var", "delta", "delta_hi",
                  "scale0", "shift0", "scale1", "shift1"):
@@ -156,7 +159,8 @@ def forward_float(x, w_base, w_cond, *, stride=1, pad=1, gate_mean=None, gate_va
 
 
 def forward_int8(x, w_base, w_cond, thr, *, stride=1, pad=1, out_i8=False, rq_mult0=None, rq_mult1=None,
-                 rq_bias=None, rq_shift=0, residual=None, rq_res_mult=0, epilogue=RELU, want_partials=True):
+                 rq_bias=None, rq_shift=0, residual=None, rq_res_mult=0, epilogue=RELU, want_partials=True,
+                 groups=1, shuffle=False):
     """Integer path: int8 inputs, int32 accumulation, int32 thresholds; exact."""
     lib = _load()
     x = _as(x, np.int8)
@@ -185,6 +189,7 @@ def forward_int8(x, w_base, w_cond, thr, *, stride=1, pad=1, out_i8=False, rq_mu
     p.n, p.h, p.w, p.c_in, p.c_out, p.c_base = n, h, w, c_in, c_out, c_base
     p.kh, p.kw, p.stride, p.pad = kh, kw, stride, pad
     p.is_int, p.out_i8, p.epilogue = 1, int(bool(out_i8)), epilogue
+    p.groups, p.shuffle = int(groups), int(bool(shuffle))
     p.xi, p.wi_base, p.wi_cond = _ptr(x, _pi8), _ptr(w_base, _pi8), _ptr(w_cond, _pi8)
     p.thr = _ptr(thr, _pi32)
     p.rq_mult0, p.rq_mult1, p.rq_bias = _ptr(rq_mult0, _pi32), _ptr(rq_mult1, _pi32), _ptr(rq_bias, _pi32)

@@ -30,6 +30,16 @@
  * The loops below are the definition written out: n, ho, wo, co, r, s, c.
  * OpenMP only spreads (n, ho) rows over threads; no blocking or reordering.
  *
+ * Channel grouping (Sec. 3.3), groups = G > 1: input and output channels are
+ * cut into G equal consecutive groups; output group i takes input group i as
+ * x_p and the other input groups, in increasing order, as x_r.  w_base then
+ * holds, for each output channel, the weights of its own input group, w_cond
+ * those of the remaining c_in - c_base channels in that order.  With
+ * shuffle != 0 the output channels are stored shuffled (Sec. 3.3, the optional
+ * ShuffleNet operation): channel j of output group i goes to position j*G + i
+ * of y (and reads the residual there); P, R, d, margin, bitmap and counts keep
+ * the natural channel order.
+ *
  * All tensors are NHWC: x[n][h][w][c_in], outputs [n][ho][wo][c_out].
  * Weights: w_base[c_out][kh][kw][c_base], w_cond[c_out][kh][kw][c_in-c_base].
  */
@@ -50,6 +60,9 @@ typedef struct cg_ref_problem {
   uint32_t epilogue;   /* CG_REF_* flags */
   int32_t two_sided;   /* float path: also require z <= delta_hi (Sec. 3.2,
                           gate for saturating activations) */
+  int32_t groups;      /* 0 or 1: x_p = first c_base channels for every output
+                          channel; G > 1: channel grouping (Sec. 3.3) */
+  int32_t shuffle;     /* grouping only: store y channel-shuffled */
 
   /* float path inputs */
   const double *x, *w_base, *w_cond;
@@ -146,6 +159,10 @@ int cg_ref_forward(const cg_ref_problem *p) {
   const int CR = C - CP;
   if (CR > 0 && (p->is_int ? !p->wi_cond : !p->w_cond)) return 1;
   const int gated = CR > 0;
+  const int G = p->groups > 1 ? p->groups : 1;
+  if (G > 1 && ((long long)CP * G != C || CO % G != 0)) return 1;
+  if (p->shuffle && G == 1) return 1;
+  const int CPG = CO / G; /* output channels per group */
   if (gated && (p->is_int ? !p->thr : (!p->gate_mean || !p->gate_var || !p->delta))) return 1;
   const int KH = p->kh, KW = p->kw, ST = p->stride, PD = p->pad;
   const int HO = cg_ref_out_h(p), WO = cg_ref_out_w(p);
@@ -164,6 +181,11 @@ int cg_ref_forward(const cg_ref_problem *p) {
         const size_t m = ((size_t)n * HO + ho) * WO + wo;
         for (int co = 0; co < CO; ++co) {
           const size_t o = m * CO + co;
+          const int grp = co / CPG;       /* output group = its base input group */
+          const int b0 = grp * CP;        /* first channel of x_p */
+          /* x_r: the channels outside [b0, b0+CP), increasing; index c sits at
+           * channel c below the gap and c + CP above it */
+          const size_t oy = p->shuffle ? m * CO + (size_t)(co % CPG) * G + grp : o;
           double accP = 0.0, accR = 0.0;
           int32_t iP = 0, iR = 0;
           uint64_t taps_in = 0;
@@ -178,11 +200,12 @@ int cg_ref_forward(const cg_ref_problem *p) {
               const size_t wbo = (((size_t)co * KH + r) * KW + s) * CP;
               const size_t wco = (((size_t)co * KH + r) * KW + s) * CR;
               if (p->is_int) {
-                for (int c = 0; c < CP; ++c) iP += (int32_t)p->xi[xo + c] * (int32_t)p->wi_base[wbo + c];
-                for (int c = 0; c < CR; ++c) iR += (int32_t)p->xi[xo + CP + c] * (int32_t)p->wi_cond[wco + c];
+                for (int c = 0; c < CP; ++c) iP += (int32_t)p->xi[xo + b0 + c] * (int32_t)p->wi_base[wbo + c];
+                for (int c = 0; c < CR; ++c)
+                  iR += (int32_t)p->xi[xo + (c < b0 ? c : c + CP)] * (int32_t)p->wi_cond[wco + c];
               } else {
-                for (int c = 0; c < CP; ++c) accP += p->x[xo + c] * p->w_base[wbo + c];
-                for (int c = 0; c < CR; ++c) accR += p->x[xo + CP + c] * p->w_cond[wco + c];
+                for (int c = 0; c < CP; ++c) accP += p->x[xo + b0 + c] * p->w_base[wbo + c];
+                for (int c = 0; c < CR; ++c) accR += p->x[xo + (c < b0 ? c : c + CP)] * p->w_cond[wco + c];
               }
             }
           }
@@ -224,15 +247,15 @@ int cg_ref_forward(const cg_ref_problem *p) {
             const int32_t s_oth = fired ? iP : iP + iR;
             if (p->Pi) p->Pi[o] = iP;
             if (p->Ri) p->Ri[o] = iR;
-            if (p->yi) p->yi[o] = finish_int(p, s_dec, fired, co, o);
-            if (p->yi_other) p->yi_other[o] = finish_int(p, s_oth, !fired, co, o);
+            if (p->yi) p->yi[oy] = finish_int(p, s_dec, fired, co, oy);
+            if (p->yi_other) p->yi_other[oy] = finish_int(p, s_oth, !fired, co, oy);
           } else {
             const double s_dec = fired ? accP + accR : accP;
             const double s_oth = fired ? accP : accP + accR;
             if (p->P) p->P[o] = accP;
             if (p->R) p->R[o] = accR;
-            if (p->y) p->y[o] = finish_float(p, s_dec, fired, co, o);
-            if (p->y_other) p->y_other[o] = finish_float(p, s_oth, !fired, co, o);
+            if (p->y) p->y[oy] = finish_float(p, s_dec, fired, co, oy);
+            if (p->y_other) p->y_other[oy] = finish_float(p, s_oth, !fired, co, oy);
           }
           if (p->margin) p->margin[o] = marg;
           if (p->d) p->d[o] = (uint8_t)(gated ? fired : 0);

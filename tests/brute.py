@@ -7,9 +7,12 @@ Follows Eq. 1 and the merged gate of Sec. 3.2 of the channel-gating paper.
 from fractions import Fraction
 
 
-def gated_conv_brute(x, w_base, w_cond, stride, pad, thr, exact=True):
+def gated_conv_brute(x, w_base, w_cond, stride, pad, thr, exact=True, groups=1):
     """x: nested list [N][H][W][C]; w_base [CO][KH][KW][CP]; w_cond [CO][KH][KW][CR];
     thr: per-channel threshold on the raw partial sum (gate fires iff P >= thr[co]).
+    groups > 1 (Sec. 3.3): the output channels are cut into `groups` equal runs; run i reads
+    input channels [i*CP, (i+1)*CP) on the base path and all the others, in order, on the
+    conditional path.
     Returns P, R, d, S as nested lists [N][HO][WO][CO] (Fractions if exact)."""
     conv = Fraction if exact else (lambda v: v)
     N, H, W = len(x), len(x[0]), len(x[0][0])
@@ -26,6 +29,9 @@ def gated_conv_brute(x, w_base, w_cond, stride, pad, thr, exact=True):
         for oh in range(HO):
             for ow in range(WO):
                 for co in range(CO):
+                    own = co // (CO // groups) if groups > 1 else 0
+                    base_ch = [own * CP + c for c in range(CP)]
+                    cond_ch = [c for c in range(CP + CR) if c not in base_ch]
                     p = conv(0)
                     q = conv(0)
                     for kh in range(KH):
@@ -34,10 +40,10 @@ def gated_conv_brute(x, w_base, w_cond, stride, pad, thr, exact=True):
                             iw = ow * stride + kw - pad
                             if not (0 <= ih < H and 0 <= iw < W):
                                 continue
-                            for c in range(CP):
-                                p += conv(x[n][ih][iw][c]) * conv(w_base[co][kh][kw][c])
-                            for c in range(CR):
-                                q += conv(x[n][ih][iw][CP + c]) * conv(w_cond[co][kh][kw][c])
+                            for c, ch in enumerate(base_ch):
+                                p += conv(x[n][ih][iw][ch]) * conv(w_base[co][kh][kw][c])
+                            for c, ch in enumerate(cond_ch):
+                                q += conv(x[n][ih][iw][ch]) * conv(w_cond[co][kh][kw][c])
                     fire = 1 if (CR == 0 or p >= thr[co]) else 0
                     P[n][oh][ow][co] = p
                     R[n][oh][ow][co] = q

@@ -361,3 +361,142 @@ def test_rejects_bad_problems():
     x = np.ones((1, 3, 3, 2))
     with pytest.raises(ValueError):
         O.forward_float(x, np.ones((1, 3, 3, 1)), np.ones((1, 3, 3, 1)))   # gated but no statistics
+
+
+# ---------------------------------------------------------------------------
+# Channel grouping (Sec. 3.3): output group i takes input group i as the base path
+# and the remaining input groups as the conditional path
+# ---------------------------------------------------------------------------
+def split_grouped(wfull, g):
+    """[CO,K,K,C] weights in input-channel order -> (w_base, w_cond) of the grouped layer, built
+    with numpy slicing/deletion only."""
+    c_out, c_in = wfull.shape[0], wfull.shape[-1]
+    cp, cpg = c_in // g, c_out // g
+    wb, wc = [], []
+    for co in range(c_out):
+        own = np.s_[(co // cpg) * cp:(co // cpg + 1) * cp]
+        wb.append(wfull[co][..., own])
+        wc.append(np.delete(wfull[co], own, axis=-1))
+    return np.ascontiguousarray(np.stack(wb)), np.ascontiguousarray(np.stack(wc))
+
+
+def lib_grouped_conv(x, w_base, g, stride, pad):
+    """torch's grouped convolution: output group i reads input group i only."""
+    xt = torch.from_numpy(np.asarray(x, np.float64)).permute(0, 3, 1, 2)
+    wt = torch.from_numpy(np.asarray(w_base, np.float64)).permute(0, 3, 1, 2)
+    return torch.nn.functional.conv2d(xt, wt, stride=stride, padding=pad, groups=g).permute(0, 2, 3, 1).numpy()
+
+
+def shuffle_channels(y, g):
+    """channel j of group i -> position j*g + i (reshape [g, c/g], transpose, flatten)."""
+    s = y.shape
+    return np.ascontiguousarray(y.reshape(s[:-1] + (g, s[-1] // g)).swapaxes(-1, -2)).reshape(s)
+
+
+@pytest.mark.parametrize("stride,pad", [(1, 1), (2, 1), (1, 0)])
+@pytest.mark.parametrize("g,c_out", [(2, 4), (4, 4), (4, 8)])
+def test_grouped_brute_force(stride, pad, g, c_out):
+    rng = np.random.default_rng(900 + 100 * stride + 10 * pad + g + c_out)
+    n, h, w, c_in = 2, 5, 6, 8
+    x = np.maximum(rng.standard_normal((n, h, w, c_in)), 0)
+    wb, wc = split_grouped(rng.standard_normal((c_out, 3, 3, c_in)) * 0.3, g)
+    mean = rng.standard_normal(c_out) * 0.1
+    var = rng.uniform(0.5, 2.0, c_out)
+    delta = rng.standard_normal(c_out) * 0.5
+    out = O.forward_float(x, wb, wc, stride=stride, pad=pad, gate_mean=mean, gate_var=var, delta=delta,
+                          epilogue=0, groups=g)
+    thr = [Fraction(float(mean[c] + delta[c] * np.sqrt(var[c]))) for c in range(c_out)]
+    P, R, D, S = gated_conv_brute(x.tolist(), wb.tolist(), wc.tolist(), stride, pad, thr, groups=g)
+    P, R, S = (np.array(a, dtype=np.float64) for a in (P, R, S))
+    D = np.array(D, dtype=np.uint8)
+    np.testing.assert_allclose(out["P"], P, rtol=0, atol=1e-12)
+    np.testing.assert_allclose(out["R"], R, rtol=0, atol=1e-12)
+    safe = np.abs(P - np.array([float(t) for t in thr])) > 1e-9
+    assert np.array_equal(out["d"][safe], D[safe]) and safe.mean() > 0.99
+    agree = out["d"] == D
+    np.testing.assert_allclose(out["y"][agree], S[agree], rtol=0, atol=1e-12)
+    # integer path, exact
+    xi = rng.integers(0, 128, (n, h, w, c_in)).astype(np.int8)
+    wbi, wci = split_grouped(rng.integers(-127, 128, (c_out, 3, 3, c_in)).astype(np.int8), g)
+    thr_i = rng.integers(-3000, 3000, c_out).astype(np.int32)
+    oi = O.forward_int8(xi, wbi, wci, thr_i, stride=stride, pad=pad, epilogue=0, groups=g)
+    P, R, D, S = gated_conv_brute(xi.tolist(), wbi.tolist(), wci.tolist(), stride, pad, thr_i.tolist(),
+                                  exact=False, groups=g)
+    assert np.array_equal(oi["P"], np.array(P)) and np.array_equal(oi["R"], np.array(R))
+    assert np.array_equal(oi["d"], np.array(D, dtype=np.uint8)) and np.array_equal(oi["y"], np.array(S))
+
+
+@pytest.mark.parametrize("stride,pad,h,w", [(1, 1, 9, 7), (2, 1, 8, 8), (1, 0, 6, 10)])
+@pytest.mark.parametrize("g", [2, 4])
+def test_grouped_extremes_match_library_convs(stride, pad, h, w, g):
+    """Never firing leaves the base path, an ordinary grouped convolution; always firing gives the
+    dense convolution with every weight back at its own input channel."""
+    rng = np.random.default_rng(77 + stride * 1000 + h * 10 + w + g)
+    n, c_in, c_out = 3, 12, 8
+    x = np.maximum(rng.standard_normal((n, h, w, c_in)), 0)
+    wfull = rng.standard_normal((c_out, 3, 3, c_in)) * 0.3
+    wb, wc = split_grouped(wfull, g)
+    mean, var = rng.standard_normal(c_out), rng.uniform(0.1, 2, c_out)
+    kw = dict(stride=stride, pad=pad, gate_mean=mean, gate_var=var, epilogue=0, groups=g)
+    hi = O.forward_float(x, wb, wc, delta=np.full(c_out, np.inf), **kw)
+    lo = O.forward_float(x, wb, wc, delta=np.full(c_out, -np.inf), **kw)
+    np.testing.assert_allclose(hi["y"], lib_grouped_conv(x, wb, g, stride, pad), rtol=1e-12, atol=1e-12)
+    np.testing.assert_allclose(lo["y"], lib_conv(x, wfull, stride, pad), rtol=1e-12, atol=1e-12)
+    assert lo["d"].all() and not hi["d"].any()
+    # a finite threshold: P is the grouped convolution, R the rest of the dense one
+    mid = O.forward_float(x, wb, wc, delta=np.zeros(c_out), **kw)
+    np.testing.assert_allclose(mid["P"], lib_grouped_conv(x, wb, g, stride, pad), rtol=1e-12, atol=1e-12)
+    np.testing.assert_allclose(mid["P"] + mid["R"], lib_conv(x, wfull, stride, pad), rtol=1e-12, atol=1e-12)
+
+
+def test_grouped_cyclic_symmetry():
+    """Rotating the input groups and the output groups together rotates the output groups."""
+    rng = np.random.default_rng(31)
+    n, h, w, c_in, c_out, g = 2, 6, 6, 8, 12, 4
+    cp, cpg = c_in // g, c_out // g
+    x = np.maximum(rng.standard_normal((n, h, w, c_in)), 0)
+    wfull = rng.standard_normal((c_out, 3, 3, c_in)) * 0.3
+    mean, var, delta = rng.standard_normal(c_out) * 0.1, rng.uniform(0.5, 2, c_out), rng.standard_normal(c_out) * 0.3
+    a = O.forward_float(x, *split_grouped(wfull, g), gate_mean=mean, gate_var=var, delta=delta, groups=g)
+    x2 = np.roll(x, cp, axis=-1)
+    w2 = np.roll(np.roll(wfull, cp, axis=-1), cpg, axis=0)
+    b = O.forward_float(x2, *split_grouped(w2, g), gate_mean=np.roll(mean, cpg), gate_var=np.roll(var, cpg),
+                        delta=np.roll(delta, cpg), groups=g)
+    np.testing.assert_allclose(b["y"], np.roll(a["y"], cpg, axis=-1), rtol=1e-12, atol=1e-12)
+    assert np.array_equal(b["d"], np.roll(a["d"], cpg, axis=-1))
+    assert 0.1 < a["d"].mean() < 0.9
+
+
+def test_grouped_shuffle_is_a_transposed_store():
+    rng = np.random.default_rng(32)
+    n, h, w, c_in, c_out, g = 2, 5, 4, 8, 12, 4
+    x = np.maximum(rng.standard_normal((n, h, w, c_in)), 0)
+    wb, wc = split_grouped(rng.standard_normal((c_out, 3, 3, c_in)) * 0.3, g)
+    mean, var, delta = rng.standard_normal(c_out) * 0.1, rng.uniform(0.5, 2, c_out), rng.standard_normal(c_out) * 0.3
+    sc = rng.uniform(0.5, 1.5, c_out)
+    res = rng.standard_normal((n, h, w, c_out))          # in the stored (shuffled) channel order
+    kw = dict(gate_mean=mean, gate_var=var, delta=delta, scale0=sc, scale1=sc * 1.1, groups=g,
+              epilogue=O.AFFINE | O.RESIDUAL | O.RELU)
+    plain = O.forward_float(x, wb, wc, residual=np.zeros_like(res), **kw)
+    pre = O.forward_float(x, wb, wc, residual=np.zeros_like(res), **dict(kw, epilogue=O.AFFINE | O.RESIDUAL))
+    shuf = O.forward_float(x, wb, wc, residual=res, shuffle=True, **kw)
+    # position j*g + i holds channel (i, j); the residual is added where the value is stored
+    np.testing.assert_allclose(shuf["y"], np.maximum(shuffle_channels(pre["y"], g) + res, 0), rtol=1e-12, atol=1e-12)
+    # decisions, bitmap and counts keep the natural channel order
+    assert np.array_equal(shuf["d"], plain["d"]) and np.array_equal(shuf["bitmap"], plain["bitmap"])
+    assert np.array_equal(shuf["counts"], plain["counts"])
+    # a known position: channel 1 of group 2 (natural index 2*3 + 1 = 7) is stored at 1*4 + 2 = 6
+    none = O.forward_float(x, wb, wc, shuffle=True, **dict(kw, epilogue=O.AFFINE))
+    nat = O.forward_float(x, wb, wc, **dict(kw, epilogue=O.AFFINE))
+    np.testing.assert_array_equal(none["y"][..., 6], nat["y"][..., 7])
+
+
+def test_grouped_rejects_bad_problems():
+    x = np.ones((1, 3, 3, 6))
+    st = dict(gate_mean=np.zeros(4), gate_var=np.ones(4), delta=np.zeros(4))
+    with pytest.raises(ValueError):   # c_base * groups != c_in
+        O.forward_float(x, np.ones((4, 3, 3, 2)), np.ones((4, 3, 3, 4)), groups=2, **st)
+    with pytest.raises(ValueError):   # c_out not a multiple of groups
+        O.forward_float(x, np.ones((4, 3, 3, 2)), np.ones((4, 3, 3, 4)), groups=3, **st)
+    with pytest.raises(ValueError):   # shuffle without grouping
+        O.forward_float(x, np.ones((4, 3, 3, 2)), np.ones((4, 3, 3, 4)), shuffle=True, **st)
