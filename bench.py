@@ -42,6 +42,9 @@ def parse():
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying a HIP graph")
     ap.add_argument("--variant", default="auto", choices=["auto", "blockskip", "compact", "rows"],
                     help="kernel family (auto = what the library picks)")
+    ap.add_argument("--grouped", action="store_true",
+                    help="channel grouping (output group i takes input group i as its base path) instead of the "
+                         "default fixed base channels")
     ap.add_argument("--layers", default="", help="comma-separated layer names to restrict the workload")
     return ap.parse_args()
 
@@ -71,7 +74,8 @@ def main():
     layers = []
     t_gen = time.perf_counter()
     for li, s in enumerate(shapes):
-        inp = W.make_inputs(s, W.seed_for(3, li), kind=args.kind, rho=args.rho, round_bf16=True)
+        inp = W.make_inputs(s, W.seed_for(3, li), kind=args.kind, rho=args.rho, round_bf16=True,
+                            grouped=args.grouped)
         gate = W.calibrate_gate(inp, args.rho, sample_images=8)
         x_bytes = s.n * s.h * s.w * s.c_in * 2
         y_bytes = s.m * s.c_out * 2
@@ -86,7 +90,7 @@ def main():
         common = dict(n_max=s.n, h=s.h, w=s.w, c_in=s.c_in, c_out=s.c_out, in_dtype=B.CG_BF16, out_dtype=B.CG_BF16,
                       stride=s.stride, pad=s.pad, epilogue=B.CG_EPI_RELU, variant=variant)
         gated = B.GatedConv(c_base=s.c_base, w_base=wb, w_cond=wc, gate_mean=gate.mean, gate_var=gate.var,
-                            delta=gate.delta, **common)
+                            delta=gate.delta, groups=s.groups if args.grouped else 0, **common)
         dense = None if args.no_dense else B.GatedConv(c_base=s.c_in, w_base=wfull, w_cond=None, **common)
         layers.append(dict(shape=s, inp=inp, gate=gate, xs=xs, ys=ys, bms=bms, gated=gated, dense=dense, nset=nset))
     torch.cuda.synchronize()
@@ -192,7 +196,7 @@ def main():
     achieved = alg_flops / (t_kernel_us * 1e-6) / 1e12
     traffic = None     # measured HBM bytes per launch, from the committed counter summary
     tfile = ROOT / "profiles" / "hbm_traffic_gated_conv_rows_kernel_imagenet_resnet18_bf16_n64.txt"
-    if (tfile.exists() and args.batch == 64 and not args.layers and args.kind == "coherent"
+    if (tfile.exists() and args.batch == 64 and not args.layers and args.kind == "coherent" and not args.grouped
             and layers[0]["gated"].variant == B.CG_VARIANT_MFMA_ROWS):
         m = re.search(r"^bytes_per_launch:\s*(\d+)", tfile.read_text(), re.M)
         traffic = int(m.group(1)) if m else None
@@ -218,7 +222,8 @@ def main():
             wb64, wc64 = inp.w_base.astype(np.float64), inp.w_cond.astype(np.float64)
             tc = time.perf_counter()
             O.forward_float(x64, wb64, wc64, stride=s.stride, pad=s.pad, gate_mean=gate.mean, gate_var=gate.var,
-                            delta=gate.delta, epilogue=O.RELU, want_partials=False)
+                            delta=gate.delta, epilogue=O.RELU, want_partials=False,
+                            groups=s.groups if args.grouped else 1)
             t_cpu += time.perf_counter() - tc
             ops_cpu += 2 * s.dense_macs
         cores = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
@@ -245,8 +250,9 @@ def main():
         "ms_per_step": round(ms_per_step, 5), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": "ImageNet-shaped ResNet-18 gated 3x3 convs (configs[2]): batch %d, bf16 NHWC, G=4, "
-                               "%s gate maps, target firing %.2f; step = all %d layers" %
-                               (args.batch, args.kind, args.rho, len(layers)),
+                               "%s gate maps, target firing %.2f%s; step = all %d layers" %
+                               (args.batch, args.kind, args.rho,
+                                ", channel grouping" if args.grouped else "", len(layers)),
                    "launch": "hip graph replay" if graph is not None else "eager",
                    "sum_us_gated": round(t_kernel_us, 2),
                    "sum_us_dense": None if args.no_dense else round(sum(L["us_dense"] for L in layers), 2),

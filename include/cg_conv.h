@@ -69,7 +69,13 @@ typedef struct cg_conv_desc {
                                 CG_I8 inputs: CG_I32 (raw sum) | CG_I8 (requantised) */
   uint32_t epilogue;         /* CG_EPI_* flags */
   int32_t variant;           /* CG_VARIANT_* */
-  int32_t reserved0;
+  int32_t groups;            /* 0 or 1: every output channel takes channels [0, c_base) of x as its base
+                                path.  G > 1: channel grouping (Sec. 3.3): input and output channels are
+                                cut into G equal consecutive groups (c_base * G == c_in, G divides c_out);
+                                output group i takes input group i as x_p and the other input groups, in
+                                increasing channel order, as x_r.  The weight layouts stay as below: per
+                                output channel, w_base holds its c_base base-path weights and w_cond the
+                                weights of its c_in - c_base conditional channels in that order. */
   int64_t x_pixel_stride;    /* elements between pixels of x; 0 means c_in */
 
   const void* w_base;        /* DEVICE [c_out][kh][kw][c_base] */
@@ -84,7 +90,10 @@ typedef struct cg_conv_desc {
   const float* delta;
   const float* delta_hi;
   float gate_eps;
-  int32_t reserved1;
+  int32_t shuffle;           /* 0 | 1, needs groups > 1: store y channel-shuffled (Sec. 3.3, the optional
+                                shuffle between grouped layers): channel j of output group i is written to
+                                position j*G + i of its pixel, and the residual is read from that position.
+                                bitmap, counts and every per-channel table keep the natural channel order. */
   /* Gate, CG_I8 inputs (HOST, [c_out]): fires iff the int32 base sum >= thr. */
   const int32_t* gate_thr_i32;
 

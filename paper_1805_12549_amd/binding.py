@@ -61,11 +61,11 @@ class cg_conv_desc(C.Structure):
         ("n_max", C.c_int32), ("h", C.c_int32), ("w", C.c_int32), ("c_in", C.c_int32), ("c_out", C.c_int32),
         ("kh", C.c_int32), ("kw", C.c_int32), ("stride", C.c_int32), ("pad", C.c_int32),
         ("c_base", C.c_int32), ("in_dtype", C.c_int32), ("out_dtype", C.c_int32),
-        ("epilogue", C.c_uint32), ("variant", C.c_int32), ("reserved0", C.c_int32),
+        ("epilogue", C.c_uint32), ("variant", C.c_int32), ("groups", C.c_int32),
         ("x_pixel_stride", C.c_int64),
         ("w_base", C.c_void_p), ("w_cond", C.c_void_p),
         ("gate_mean", _pf), ("gate_var", _pf), ("delta", _pf), ("delta_hi", _pf),
-        ("gate_eps", C.c_float), ("reserved1", C.c_int32),
+        ("gate_eps", C.c_float), ("shuffle", C.c_int32),
         ("gate_thr_i32", _pi),
         ("scale0", _pf), ("shift0", _pf), ("scale1", _pf), ("shift1", _pf),
         ("rq_mult0", _pi), ("rq_mult1", _pi), ("rq_bias", _pi),
@@ -165,6 +165,7 @@ class GatedConv:
 
     w_base / w_cond: torch device tensors [C_out,kh,kw,C_base] / [C_out,kh,kw,C_in-C_base] in the
     input dtype (bf16 tensors for CG_BF16, int8 for CG_I8, float32 for CG_F32).
+    groups > 1 selects channel grouping, shuffle the channel-shuffled store (see cg_conv.h).
     """
 
     def __init__(self, *, n_max, h, w, c_in, c_out, c_base, w_base, w_cond, in_dtype, out_dtype,
@@ -172,7 +173,7 @@ class GatedConv:
                  gate_mean=None, gate_var=None, delta=None, delta_hi=None, gate_eps=0.0, gate_thr_i32=None,
                  scale0=None, shift0=None, scale1=None, shift1=None,
                  rq_mult0=None, rq_mult1=None, rq_bias=None, rq_shift=0, rq_res_mult=0,
-                 x_pixel_stride=0, stream=None):
+                 x_pixel_stride=0, groups=0, shuffle=False, stream=None):
         import torch
         self._torch = torch
         self.handle = None
@@ -182,6 +183,7 @@ class GatedConv:
         d.kh, d.kw, d.stride, d.pad, d.c_base = kh, kw, stride, pad, c_base
         d.in_dtype, d.out_dtype, d.epilogue, d.variant = in_dtype, out_dtype, epilogue, variant
         d.x_pixel_stride = x_pixel_stride
+        d.groups, d.shuffle = int(groups), int(bool(shuffle))
         self._keep = [w_base, w_cond]
         d.w_base = w_base.data_ptr()
         d.w_cond = w_cond.data_ptr() if (w_cond is not None and w_cond.numel()) else None

@@ -77,6 +77,15 @@ int validate(const cg_conv_desc* d, int* ho, int* wo) {
     return fail(CG_EUNSUPPORTED, "kernel size %dx%d: only 3x3 and 1x1 are supported", d->kh, d->kw);
   if (d->pad >= d->kh && d->pad > 0) return fail(CG_EINVAL, "pad %d must be smaller than the kernel size", d->pad);
   if (d->c_base <= 0 || d->c_base > d->c_in) return fail(CG_EINVAL, "c_base must lie in (0, c_in]");
+  if (d->groups < 0) return fail(CG_EINVAL, "groups must be >= 0");
+  if (d->groups > 1) {
+    if ((long long)d->c_base * d->groups != d->c_in)
+      return fail(CG_EINVAL, "channel grouping needs c_base * groups == c_in (%d * %d != %d)", d->c_base, d->groups,
+                  d->c_in);
+    if (d->c_out % d->groups) return fail(CG_EINVAL, "channel grouping needs groups to divide c_out");
+  }
+  if (d->shuffle != 0 && d->shuffle != 1) return fail(CG_EINVAL, "shuffle must be 0 or 1");
+  if (d->shuffle && d->groups <= 1) return fail(CG_EINVAL, "shuffle needs channel grouping (groups > 1)");
   if (d->in_dtype != CG_F32 && d->in_dtype != CG_BF16 && d->in_dtype != CG_I8)
     return fail(CG_EINVAL, "in_dtype must be CG_F32, CG_BF16 or CG_I8");
   if (d->in_dtype == CG_I8) {
@@ -314,6 +323,8 @@ int cg_conv_create(cg_conv** out, const cg_conv_desc* desc, void* hip_stream) {
     p.kh = d.kh;
     p.kw = d.kw;
     p.in_dtype = d.in_dtype;
+    p.groups = d.groups > 1 ? d.groups : 1;
+    p.cpg = d.c_out / p.groups;
     p.w_base = pk + lay.w_base_off;
     p.w_cond = pk + lay.w_cond_off;
     if (variant == CG_VARIANT_MFMA)
@@ -391,14 +402,10 @@ int cg_conv_forward(cg_conv* h, int32_t n, const void* x, const void* residual, 
   p.rq_shift = d.rq_shift;
   p.rq_res_mult = d.rq_res_mult;
   p.words = (d.c_out + 31) / 32;
-#ifdef CG_PROFILE_KNOBS
-  {  // developer builds only: switches off parts of the kernel to time the rest (results are then wrong)
-    const char* dbg = getenv("CG_DEBUG_SKIP");
-    p.debug = dbg ? atoi(dbg) : 0;
-  }
-#else
+  p.groups = d.groups > 1 ? d.groups : 1;
+  p.cpg = d.c_out / p.groups;
+  p.shuffle = d.shuffle;
   p.debug = 0;
-#endif
   const size_t ts = l.table_stride;
   p.thr_f = (const float*)(pk + 0 * ts);
   p.thr_hi_f = (const float*)(pk + 1 * ts);
@@ -429,7 +436,7 @@ int cg_conv_forward(cg_conv* h, int32_t n, const void* x, const void* residual, 
       p.bitmap = (uint32_t*)workspace;
     }
     if (e == hipSuccess) e = cg::launch_mfma3(h->plan3, p, pk + l.wpk_base_off, pk + l.wpk_cond_off, s);
-    if (e == hipSuccess && counts && p.gated && !(p.debug & 16)) e = cg::launch_bitmap_counts(p, p.bitmap, s);
+    if (e == hipSuccess && counts && p.gated) e = cg::launch_bitmap_counts(p, p.bitmap, s);
   } else if (e == hipSuccess) {
     if (h->variant == CG_VARIANT_MFMA_COMPACT)
       e = cg::launch_mfma2(h->plan2, p, pk + l.wpk_base_off, pk + l.wpk_cond_off, s);

@@ -21,6 +21,9 @@ struct Params {
   int gated;               // 0: dense layer, no gate, second affine pair applies
   int rq_shift, rq_res_mult;
   int words;               // bitmap words per pixel = ceil(c_out/32)
+  int groups;              // >= 1; > 1: channel grouping (Sec. 3.3), output group i has input group i as base
+  int cpg;                 // output channels per group = c_out / groups
+  int shuffle;             // y (and the residual) in shuffled channel order: channel j of group i at j*groups + i
   int debug;               // profiling knobs (CG_DEBUG_SKIP): results are wrong when non-zero
 
   // per-output-channel tables, device, in `packed`
@@ -129,6 +132,12 @@ struct Mfma3Plan {
   int cps;                 // chunks per pixel per super-stage: 4 or 2
   int ni;                  // 1 KB load instructions per super-stage patch = ceil(pr * pitch * cps / 64)
   int pkb;                 // LDS patch buffer class: 24 KB (two workgroups per CU) or 48 KB
+  // Channel grouping.  0: none.  1: a 64-channel block lies inside one output group; its base
+  // channels start at group*c_base and the conditional phase skips them.  2: a block covers
+  // `gsp` whole groups; its base phase walks the gsp*c_base base channels of all of them and its
+  // conditional phase all c_in channels, the packed weights holding zeros where a channel is not on
+  // that path for that output channel.
+  int grp_mode, gsp;
   int stages[2];           // super-stages of the base / conditional phase
   size_t wpk_base_bytes, wpk_cond_bytes;
 };

@@ -305,11 +305,24 @@ __global__ __launch_bounds__(NWV * 64, PKB == 12 ? 3 : 2) void gated_conv_rows_k
   const int np0 = __popc(smask & ((1u << KH) - 1u));
   const int np1 = __popc((smask >> KH) & ((1u << (KPW - KH)) - 1u));
 
-  // x at the first channel of super-stage sg (counted over both phases)
+  // x at the first channel of super-stage sg (counted over both phases).  The base phase starts at
+  // this block's first base channel; the conditional phase walks the channels in order and jumps
+  // over the base channels (without grouping these are the first c_base; with grouping, Sec. 3.3,
+  // those of the block's own group, or none when the block covers several groups and the packed
+  // weights carry zeros instead).
+  int base_ch0 = 0, gap_start = 0, gap_len = p.c_base;
+  if (g.grp_mode == 1) {
+    base_ch0 = gap_start = (cbk * kBn / p.cpg) * p.c_base;
+  } else if (g.grp_mode == 2) {
+    base_ch0 = cbk * g.gsp * p.c_base;
+    gap_len = 0;
+  }
   auto x_src = [&](int sg) __attribute__((always_inline)) {
     const int ph = sg >= S0 ? 1 : 0;
     const int ss = ph ? sg - S0 : sg;
-    return xbytes + (long long)((ph ? p.c_base : 0) + ss * CPS * g.ch) * eb;
+    int chn = ss * CPS * g.ch;
+    chn = ph ? (chn >= gap_start ? chn + gap_len : chn) : base_ch0 + chn;
+    return xbytes + (long long)chn * eb;
   };
   {
     const char* xs0 = x_src(0);
@@ -597,7 +610,30 @@ __global__ __launch_bounds__(NWV * 64, PKB == 12 ? 3 : 2) void gated_conv_rows_k
 
   // ---- output function on 16 consecutive channels per accumulator ---------------------------------
   const int ob = p.out_dtype == CG_BF16 ? 2 : p.out_dtype == CG_I8 ? 1 : 4;
-  if (ob == 4) {
+  if (p.shuffle) {
+    // shuffled channel order (Sec. 3.3): channel j of group i goes to position j*groups + i of its
+    // pixel, one element at a time
+#pragma unroll
+    for (int fp = 0; fp < NF; ++fp) {
+      if (!pval[fp]) continue;
+#pragma unroll
+      for (int fc = 0; fc < 2; ++fc) {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+          const int co = cbk * kBn + 32 * fc + 16 * lh + i;
+          const int grp = co / p.cpg;
+          const long long o = (m0 + pix[fp]) * p.c_out + (co - grp * p.cpg) * p.groups + grp;
+          const bool fired = p.gated ? ((dlane[fp] >> (16 * fc + i)) & 1u) != 0u : true;
+          const acc_t sv = accP[fp][fc][i];
+          if constexpr (Base::kDtype == CG_I8) {
+            store_int(p, o, finish_int(p, sv, fired, co, o));
+          } else {
+            store_float(p, o, finish_float(p, sv, fired, co, o));
+          }
+        }
+      }
+    }
+  } else if (ob == 4) {
     // 4-byte outputs: a lane's 16 channels are 64 contiguous bytes; stored directly
 #pragma unroll
     for (int fp = 0; fp < NF; ++fp) {
@@ -692,8 +728,13 @@ __global__ __launch_bounds__(NWV * 64, PKB == 12 ? 3 : 2) void gated_conv_rows_k
 // with tap = 3r + k / (CPS/2) and chunk = CPS*sigma + 2*(k % (CPS/2)) + h; row rho of a 32-row
 // fragment holds channel 16*((rho/4)%2) + 4*(rho/8) + rho%4, which puts 16 consecutive channels in
 // one lane of the transposed product
+//
+// Channel grouping with blocks that cover several groups (multi != 0): the base phase (phase 0)
+// walks the base channels of all the block's groups, the conditional phase all c_in channels; a
+// chunk that is not on that path for the row's output channel is packed as zeros (a chunk never
+// straddles a group: c_base is a multiple of the chunk's channel count).
 __global__ void pack_rows_kernel(const char* __restrict__ w, char* __restrict__ out, int c_phase, int eb, int ch,
-                                 int cps, int stages, long long total) {
+                                 int cps, int stages, long long total, int multi, int phase, int c_base, int cpg) {
   const long long id = (long long)blockIdx.x * blockDim.x + threadIdx.x;
   if (id >= total) return;
   const int gk = 3 * cps / 2, pairs = cps / 2;
@@ -711,8 +752,22 @@ __global__ void pack_rows_kernel(const char* __restrict__ w, char* __restrict__ 
   const int chunk = cps * ss + 2 * (k % pairs) + h;
   const int fc = rho >> 5, rr = rho & 31;
   const int co = cb * kBn + 32 * fc + 16 * ((rr >> 2) & 1) + 4 * (rr >> 3) + (rr & 3);
-  const char* src = w + (((long long)co * 9 + tap) * c_phase + chunk * ch) * eb;
-  *(i32x4*)(out + id * 16) = *(const i32x4*)src;
+  int c_src = chunk * ch;          // first channel of the chunk in the row's w_base / w_cond
+  bool zero = false;
+  if (multi) {
+    const int grp = co / cpg;      // the row's output group = its base input group
+    if (phase == 0) {
+      const int blk_grp0 = (cb * kBn) / cpg;                 // first group of this column block
+      zero = blk_grp0 + c_src / c_base != grp;
+      c_src = c_src % c_base;
+    } else {
+      zero = c_src / c_base == grp;
+      if (c_src >= (grp + 1) * c_base) c_src -= c_base;
+    }
+  }
+  i32x4 v = {0, 0, 0, 0};
+  if (!zero) v = *(const i32x4*)(w + (((long long)co * 9 + tap) * c_phase + c_src) * eb);
+  *(i32x4*)(out + id * 16) = v;
 }
 
 // per-(image, channel) fired counts and their total from the decision bitmap
@@ -791,12 +846,28 @@ Mfma3Plan mfma3_plan(const cg_conv_desc& d) {
   if (d.stride < 1 || d.stride > 2 || d.pad > 1) return g;
   g.elem_bytes = d.in_dtype == CG_BF16 ? 2 : 1;
   g.ch = 16 / g.elem_bytes;
-  const int c_cond = d.c_in - d.c_base;
   const long long xps = d.x_pixel_stride ? d.x_pixel_stride : d.c_in;
   if (xps % g.ch) return g;
-  if (d.c_base % (4 * g.ch) == 0 && c_cond % (4 * g.ch) == 0)
+  // channels the two phases walk
+  int base_k = d.c_base, c_cond = d.c_in - d.c_base;
+  g.grp_mode = 0;
+  g.gsp = 1;
+  if (d.groups > 1) {
+    const int cpg = d.c_out / d.groups;
+    if (cpg % kBn == 0) {
+      g.grp_mode = 1;                       // a 64-channel block lies inside one group
+    } else if (kBn % cpg == 0 && d.c_base % g.ch == 0) {
+      g.grp_mode = 2;                       // a block covers kBn/cpg whole groups
+      g.gsp = kBn / cpg;
+      base_k = g.gsp * d.c_base;
+      c_cond = d.c_in;
+    } else {
+      return g;
+    }
+  }
+  if (base_k % (4 * g.ch) == 0 && c_cond % (4 * g.ch) == 0)
     g.cps = 4;
-  else if (d.c_base % (2 * g.ch) == 0 && c_cond % (2 * g.ch) == 0)
+  else if (base_k % (2 * g.ch) == 0 && c_cond % (2 * g.ch) == 0)
     g.cps = 2;
   else
     return g;
@@ -875,7 +946,7 @@ Mfma3Plan mfma3_plan(const cg_conv_desc& d) {
       g.pkb = c.pkb;
       g.pr = patch_rows(t);
       g.ni = (g.pr * P * g.cps + 63) / 64;
-      g.stages[0] = d.c_base / (g.cps * g.ch);
+      g.stages[0] = base_k / (g.cps * g.ch);
       g.stages[1] = c_cond / (g.cps * g.ch);
       const size_t gb = (size_t)(3 * g.cps / 2) * 2048;
       g.wpk_base_bytes = (size_t)g.n_cb * g.stages[0] * 3 * gb;
@@ -894,7 +965,7 @@ hipError_t launch_mfma3_pack(const Mfma3Plan& g, const Params& p, void* wpk_base
     const unsigned blocks = (unsigned)((total + 255) / 256);
     hipLaunchKernelGGL(pack_rows_kernel, dim3(blocks), dim3(256), 0, s, (const char*)(ph ? p.w_cond : p.w_base),
                        (char*)(ph ? wpk_cond : wpk_base), ph ? p.c_cond : p.c_base, g.elem_bytes, g.ch, g.cps,
-                       g.stages[ph], total);
+                       g.stages[ph], total, g.grp_mode == 2 ? 1 : 0, ph, p.c_base, p.cpg);
     const hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
   }

@@ -2,7 +2,9 @@
 // Covers every shape and dtype the API accepts (fp32 layers, channel counts
 // the matrix-core kernels cannot tile, any kernel size).  Follows Eq. 1 of
 // the channel-gating paper step by step: base sum, gate, conditional sum only
-// where the gate fired, output function.
+// where the gate fired, output function.  With channel grouping (Sec. 3.3) the
+// base channels of output group i are input group i and the conditional
+// channels are all the others in increasing order.
 #include "cg_device.h"
 
 namespace cg {
@@ -50,6 +52,9 @@ __global__ __launch_bounds__(256) void naive_kernel(Params p) {
     const T* wb = (const T*)p.w_base + (long long)co * p.kh * p.kw * p.c_base;
     const T* wc = (const T*)p.w_cond + (long long)co * p.kh * p.kw * p.c_cond;
 
+    const int grp = co / p.cpg;           // 0 without grouping
+    const int b0 = grp * p.c_base;        // first base-path channel of this output channel
+
     acc_t acc = 0;
     for (int r = 0; r < p.kh; ++r) {
       const int hi = ho * p.stride - p.pad + r;
@@ -59,7 +64,7 @@ __global__ __launch_bounds__(256) void naive_kernel(Params p) {
         if (wi < 0 || wi >= p.w) continue;
         const long long xo = (((long long)img * p.h + hi) * p.w + wi) * p.x_pixel_stride;
         const int wofs = (r * p.kw + s) * p.c_base;
-        for (int c = 0; c < p.c_base; ++c) acc = E::mul_add(E::get(x, xo + c), E::get(wb, wofs + c), acc);
+        for (int c = 0; c < p.c_base; ++c) acc = E::mul_add(E::get(x, xo + b0 + c), E::get(wb, wofs + c), acc);
       }
     }
 
@@ -76,15 +81,18 @@ __global__ __launch_bounds__(256) void naive_kernel(Params p) {
           for (int s = 0; s < p.kw; ++s) {
             const int wi = wo * p.stride - p.pad + s;
             if (wi < 0 || wi >= p.w) continue;
-            const long long xo = (((long long)img * p.h + hi) * p.w + wi) * p.x_pixel_stride + p.c_base;
+            const long long xo = (((long long)img * p.h + hi) * p.w + wi) * p.x_pixel_stride;
             const int wofs = (r * p.kw + s) * p.c_cond;
-            for (int c = 0; c < p.c_cond; ++c) acc = E::mul_add(E::get(x, xo + c), E::get(wc, wofs + c), acc);
+            // conditional channel c is input channel c below the base channels, c + c_base above
+            for (int c = 0; c < b0; ++c) acc = E::mul_add(E::get(x, xo + c), E::get(wc, wofs + c), acc);
+            for (int c = b0; c < p.c_cond; ++c)
+              acc = E::mul_add(E::get(x, xo + p.c_base + c), E::get(wc, wofs + c), acc);
           }
         }
       }
     }
 
-    const long long o = m * p.c_out + co;
+    const long long o = m * p.c_out + (p.shuffle ? (co - grp * p.cpg) * p.groups + grp : co);
     const bool branch1 = p.gated ? fired : true;
     if constexpr (__is_same(acc_t, float)) {
       store_float(p, o, finish_float(p, acc, branch1, co, o));

@@ -139,10 +139,31 @@ class LayerInputs:
     x: np.ndarray        # float32 [N,H,W,C_in]
     w_base: np.ndarray   # float32 [C_out,3,3,C_base]
     w_cond: np.ndarray   # float32 [C_out,3,3,C_in-C_base]
+    grouped: bool = False   # channel grouping: output group i has input group i as its base channels
+
+
+def split_weights(wfull: np.ndarray, c_base: int, grouped: bool):
+    """[C_out,k,k,C_in] weights in input-channel order -> (w_base, w_cond) in the layer's layouts.
+    Ungrouped: the first c_base input channels are every output channel's base channels.  Grouped:
+    with G = C_in / c_base groups, output channel co of group i = co // (C_out/G) takes input
+    channels [i*c_base, (i+1)*c_base) as base and the others, in order, as conditional channels."""
+    c_out, c_in = wfull.shape[0], wfull.shape[-1]
+    if not grouped:
+        return np.ascontiguousarray(wfull[..., :c_base]), np.ascontiguousarray(wfull[..., c_base:])
+    g = c_in // c_base
+    cpg = c_out // g
+    own = (np.arange(c_out) // cpg)[:, None] * c_base + np.arange(c_base)[None, :]       # [C_out, c_base]
+    mask = np.ones((c_out, c_in), bool)
+    np.put_along_axis(mask, own, False, axis=1)
+    rest = np.nonzero(mask)[1].reshape(c_out, c_in - c_base)                               # increasing per row
+    idx_b = np.broadcast_to(own[:, None, None, :], wfull.shape[:3] + (c_base,))
+    idx_r = np.broadcast_to(rest[:, None, None, :], wfull.shape[:3] + (c_in - c_base,))
+    return (np.ascontiguousarray(np.take_along_axis(wfull, idx_b, axis=-1)),
+            np.ascontiguousarray(np.take_along_axis(wfull, idx_r, axis=-1)))
 
 
 def make_inputs(shape: LayerShape, seed: int, kind: str = "iid", rho: float = 0.3,
-                round_bf16: bool = False, dc: float = 2.0) -> LayerInputs:
+                round_bf16: bool = False, dc: float = 2.0, grouped: bool = False) -> LayerInputs:
     """kind: 'iid'      x = relu(N(0,1)), Kaiming-normal weights;
              'literal'  x additionally scaled by a smooth per-image magnitude field
                         (min-max normalised Gaussian-blurred uniform noise, sigma 4 px);
@@ -166,29 +187,37 @@ def make_inputs(shape: LayerShape, seed: int, kind: str = "iid", rho: float = 0.
             on = min(1.0, rho + 0.10)
             q = np.quantile(f, 1.0 - on) if on < 1.0 else f.min() - 1.0
             mfield = np.clip((f - q) / 0.05 + 0.5, 0.0, 1.0)
-            wfull[..., : s.c_base] += np.float32(dc * std)
+            if grouped:
+                cpg = s.c_out // s.groups
+                for i in range(s.groups):      # the DC term sits on each output group's own base weights
+                    wfull[i * cpg:(i + 1) * cpg, ..., i * s.c_base:(i + 1) * s.c_base] += np.float32(dc * std)
+            else:
+                wfull[..., : s.c_base] += np.float32(dc * std)
         x = x * mfield[..., None].astype(np.float32)
     elif kind != "iid":
         raise ValueError(kind)
     if round_bf16:
         x = bf16_round(x)
         wfull = bf16_round(wfull)
-    w_base = np.ascontiguousarray(wfull[..., : s.c_base])
-    w_cond = np.ascontiguousarray(wfull[..., s.c_base:])
-    return LayerInputs(s, kind, np.ascontiguousarray(x), w_base, w_cond)
+    w_base, w_cond = split_weights(wfull, s.c_base, grouped)
+    return LayerInputs(s, kind, np.ascontiguousarray(x), w_base, w_cond, grouped)
 
 
 # ----------------------------------------------------------------------------
 # gate statistics (inputs of the layer; calibrated with a library convolution)
 # ----------------------------------------------------------------------------
 
-def _library_partial_sums(x: np.ndarray, w_base: np.ndarray, stride: int, pad: int) -> np.ndarray:
-    """Base-path sums over the given images from torch's CPU convolution, float64, [n,ho,wo,c_out]."""
+def _library_partial_sums(x: np.ndarray, w_base: np.ndarray, stride: int, pad: int,
+                          grouped: bool = False) -> np.ndarray:
+    """Base-path sums over the given images from torch's CPU convolution (its grouped convolution
+    for a grouped layer), float64, [n,ho,wo,c_out]."""
     import torch
     c_base = w_base.shape[-1]
-    xt = torch.from_numpy(np.ascontiguousarray(x[..., :c_base], dtype=np.float64)).permute(0, 3, 1, 2)
+    groups = x.shape[-1] // c_base if grouped else 1
+    xin = x if grouped else x[..., :c_base]
+    xt = torch.from_numpy(np.ascontiguousarray(xin, dtype=np.float64)).permute(0, 3, 1, 2)
     wt = torch.from_numpy(np.ascontiguousarray(w_base, dtype=np.float64)).permute(0, 3, 1, 2)
-    p = torch.nn.functional.conv2d(xt, wt, stride=stride, padding=pad)
+    p = torch.nn.functional.conv2d(xt, wt, stride=stride, padding=pad, groups=groups)
     return p.permute(0, 2, 3, 1).contiguous().numpy()
 
 
@@ -206,7 +235,7 @@ def calibrate_gate(inp: LayerInputs, rho: float, sample_images: Optional[int] = 
     (1-rho) quantile of the normalised sums, so that about a fraction rho of gates fire."""
     s = inp.shape
     k = s.n if sample_images is None else min(s.n, sample_images)
-    p = _library_partial_sums(inp.x[:k], inp.w_base, s.stride, s.pad).reshape(-1, s.c_out)
+    p = _library_partial_sums(inp.x[:k], inp.w_base, s.stride, s.pad, inp.grouped).reshape(-1, s.c_out)
     mean = p.mean(axis=0)
     var = p.var(axis=0)
     z = (p - mean) / np.sqrt(np.maximum(var, 1e-300))
@@ -234,6 +263,7 @@ class Int8Inputs:
     w_cond: np.ndarray   # int8
     s_x: float
     s_w: np.ndarray      # float64 [C_out]
+    grouped: bool = False
 
 
 def quantize_int8(inp: LayerInputs) -> Int8Inputs:
@@ -245,14 +275,14 @@ def quantize_int8(inp: LayerInputs) -> Int8Inputs:
     sw4 = s_w.astype(np.float32)[:, None, None, None]
     wb = np.clip(np.rint(inp.w_base / sw4), -127, 127).astype(np.int8)
     wc = np.clip(np.rint(inp.w_cond / sw4), -127, 127).astype(np.int8)
-    return Int8Inputs(inp.shape, xq, wb, wc, s_x, s_w)
+    return Int8Inputs(inp.shape, xq, wb, wc, s_x, s_w, inp.grouped)
 
 
 def calibrate_gate_int8(q: Int8Inputs, rho: float, sample_images: Optional[int] = 8) -> np.ndarray:
     """Integer threshold per output channel: ceil(E + Delta*sigma) of the integer base sums."""
     s = q.shape
     k = s.n if sample_images is None else min(s.n, sample_images)
-    p = _library_partial_sums(q.x[:k].astype(np.float64), q.w_base.astype(np.float64), s.stride, s.pad)
+    p = _library_partial_sums(q.x[:k].astype(np.float64), q.w_base.astype(np.float64), s.stride, s.pad, q.grouped)
     p = p.reshape(-1, s.c_out)
     mean = p.mean(axis=0)
     sd = np.sqrt(p.var(axis=0))

@@ -47,9 +47,11 @@ def bf16_ulp(v):
 
 def run_float(inp: W.LayerInputs, gate: W.GateParams, *, in_dtype=B.CG_BF16, out_dtype=B.CG_F32,
               epilogue=B.CG_EPI_RELU, variant=B.CG_VARIANT_AUTO, affine=None, residual=None, delta_hi=None,
-              n_run=None, name="", check_counts=True):
-    """Runs the GPU library and the oracle; asserts parity; returns a Report."""
+              n_run=None, name="", check_counts=True, shuffle=False):
+    """Runs the GPU library and the oracle; asserts parity; returns a Report.  A grouped input set
+    (inp.grouped) runs the layer with channel grouping; shuffle stores y channel-shuffled."""
     s = inp.shape
+    groups = s.groups if inp.grouped else 1
     tdt = torch.bfloat16 if in_dtype == B.CG_BF16 else torch.float32
     odt = torch.bfloat16 if out_dtype == B.CG_BF16 else torch.float32
     x = _dev(inp.x, tdt)
@@ -62,7 +64,7 @@ def run_float(inp: W.LayerInputs, gate: W.GateParams, *, in_dtype=B.CG_BF16, out
                         stride=s.stride, pad=s.pad, epilogue=epilogue, variant=variant,
                         gate_mean=gate.mean if gate else None, gate_var=gate.var if gate else None,
                         delta=gate.delta if gate else None, delta_hi=delta_hi, gate_eps=gate.eps if gate else 0.0,
-                        **aff)
+                        groups=groups, shuffle=shuffle, **aff)
     n = s.n if n_run is None else n_run
     res_dev = None
     res_host = None
@@ -87,11 +89,15 @@ def run_float(inp: W.LayerInputs, gate: W.GateParams, *, in_dtype=B.CG_BF16, out
         gate_eps=float(np.float32(gate.eps)) if gate else 0.0,
         scale0=f32(aff.get("scale0")), shift0=f32(aff.get("shift0")),
         scale1=f32(aff.get("scale1")), shift1=f32(aff.get("shift1")),
-        residual=res_host, epilogue=epilogue, want_partials=False)
-    return compare_float(name or s.name, y, bitmap, counts, ref, s.c_out, out_dtype, variant_used, check_counts)
+        residual=res_host, epilogue=epilogue, want_partials=False, groups=groups, shuffle=shuffle)
+    return compare_float(name or s.name, y, bitmap, counts, ref, s.c_out, out_dtype, variant_used, check_counts,
+                         stored_groups=groups if shuffle else 0)
 
 
-def compare_float(name, y, bitmap, counts, ref, c_out, out_dtype, variant_used, check_counts=True):
+def compare_float(name, y, bitmap, counts, ref, c_out, out_dtype, variant_used, check_counts=True,
+                  stored_groups=0):
+    """stored_groups = G > 0: y holds the channels shuffled (channel j of group i at j*G + i) while
+    the decisions keep the natural order."""
     d_gpu = W.unpack_bitmap(bitmap, c_out).reshape(ref["d"].shape)
     d_ref = ref["d"]
     flip = d_gpu != d_ref
@@ -102,7 +108,11 @@ def compare_float(name, y, bitmap, counts, ref, c_out, out_dtype, variant_used, 
     # unused bitmap bits must be zero
     if c_out % 32:
         assert (bitmap[:, -1] >> np.uint32(c_out % 32) == 0).all(), "%s: unused bitmap bits set" % name
-    want = np.where(flip, ref["y_other"], ref["y"])
+    flip_y = flip
+    if stored_groups:
+        sh = flip.shape
+        flip_y = flip.reshape(sh[:-1] + (stored_groups, c_out // stored_groups)).swapaxes(-1, -2).reshape(sh)
+    want = np.where(flip_y, ref["y_other"], ref["y"])
     tol = ATOL + RTOL * np.abs(want)
     if out_dtype == B.CG_BF16:
         tol = tol + bf16_ulp(want)
@@ -119,8 +129,9 @@ def compare_float(name, y, bitmap, counts, ref, c_out, out_dtype, variant_used, 
 
 
 def run_int8(q: W.Int8Inputs, thr, *, out_i8=False, epilogue=B.CG_EPI_RELU, variant=B.CG_VARIANT_AUTO,
-             rq=None, residual=None, rq_res_mult=0, n_run=None, name=""):
+             rq=None, residual=None, rq_res_mult=0, n_run=None, name="", shuffle=False):
     s = q.shape
+    groups = s.groups if q.grouped else 1
     x = _dev(q.x, torch.int8)
     wb = _dev(q.w_base, torch.int8)
     wc = _dev(q.w_cond, torch.int8) if q.w_cond.shape[-1] else None
@@ -129,7 +140,7 @@ def run_int8(q: W.Int8Inputs, thr, *, out_i8=False, epilogue=B.CG_EPI_RELU, vari
     layer = B.GatedConv(n_max=s.n, h=s.h, w=s.w, c_in=s.c_in, c_out=s.c_out, c_base=q.w_base.shape[-1],
                         w_base=wb, w_cond=wc, in_dtype=B.CG_I8, out_dtype=B.CG_I8 if out_i8 else B.CG_I32,
                         kh=k, kw=k, stride=s.stride, pad=s.pad, epilogue=epilogue, variant=variant,
-                        gate_thr_i32=thr, rq_res_mult=rq_res_mult, **rq)
+                        gate_thr_i32=thr, rq_res_mult=rq_res_mult, groups=groups, shuffle=shuffle, **rq)
     n = s.n if n_run is None else n_run
     res_dev = _dev(residual[:n], torch.int8) if residual is not None else None
     y, bitmap, counts = layer.forward(x[:n], residual=res_dev)
@@ -141,7 +152,8 @@ def run_int8(q: W.Int8Inputs, thr, *, out_i8=False, epilogue=B.CG_EPI_RELU, vari
     layer.close()
     ref = O.forward_int8(q.x[:n], q.w_base, q.w_cond if wc is not None else None, thr, stride=s.stride, pad=s.pad,
                          out_i8=out_i8, residual=residual[:n] if residual is not None else None,
-                         rq_res_mult=rq_res_mult, epilogue=epilogue, want_partials=False, **rq)
+                         rq_res_mult=rq_res_mult, epilogue=epilogue, want_partials=False, groups=groups,
+                         shuffle=shuffle, **rq)
     nm = name or s.name
     assert np.array_equal(bitmap, ref["bitmap"]), "%s: bitmap differs in %d words" % (
         nm, int((bitmap != ref["bitmap"]).sum()))

@@ -32,6 +32,18 @@ def test_imagenet_bf16_batch64(li):
     assert rep.flips < 1000
 
 
+@pytest.mark.parametrize("li", range(len(IMAGENET)), ids=[s.name for s in IMAGENET])
+def test_imagenet_grouped_bf16_batch64(li):
+    """The same layers with channel grouping, as `bench.py --grouped` launches them."""
+    shape = IMAGENET[li]
+    inp = W.make_inputs(shape, W.seed_for(3, li), kind="coherent", rho=0.30, round_bf16=True, grouped=True)
+    gate = W.calibrate_gate(inp, 0.30, sample_images=8)
+    rep = _say(P.run_float(inp, gate, in_dtype=B.CG_BF16, out_dtype=B.CG_BF16, name=shape.name + " N=64 grouped"))
+    assert rep.variant == B.CG_VARIANT_MFMA_ROWS
+    assert 0.15 < rep.fired_frac < 0.5
+    assert rep.flips < 1000
+
+
 def test_imagenet_literal_maps_fp32_out():
     shape = IMAGENET[1]
     inp = W.make_inputs(shape, W.seed_for(3, 11), kind="literal", rho=0.35, round_bf16=True)
