@@ -50,6 +50,7 @@ class _Problem(C.Structure):
         ("kh", C.c_int32), ("kw", C.c_int32), ("stride", C.c_int32), ("pad", C.c_int32),
         ("is_int", C.c_int32), ("out_i8", C.c_int32), ("epilogue", C.c_uint32),
         ("two_sided", C.c_int32), ("groups", C.c_int32), ("shuffle", C.c_int32),
+        ("tau_c", C.c_double),
         ("x", _pd), ("w_base", _pd), ("w_cond", _pd),
         ("gate_mean", _pd), ("gate_var", _pd), ("delta", _pd), ("delta_hi", _pd),
         ("gate_eps", C.c_double),
@@ -61,6 +62,7 @@ class _Problem(C.Structure):
         ("P", _pd), ("R", _pd), ("y", _pd), ("y_other", _pd), ("margin", _pd),
         ("Pi", _pi32), ("Ri", _pi32), ("yi", _pi32), ("yi_other", _pi32),
         ("d", _pu8), ("bitmap", _pu32), ("counts", _pu32), ("macs", _pu64),
+        ("pre_counts", _pu32),
     ]
 
 
@@ -93,11 +95,13 @@ def _ptr(a, ptype):
 
 def forward_float(x, w_base, w_cond, *, stride=1, pad=1, gate_mean=None, gate_var=None, delta=None,
                   delta_hi=None, gate_eps=0.0, scale0=None, shift0=None, scale1=None, shift1=None,
-                  residual=None, epilogue=RELU, want_partials=True, groups=1, shuffle=False):
+                  residual=None, epilogue=RELU, want_partials=True, groups=1, shuffle=False, tau_c=0.0):
     """Float path.  x [N,H,W,C_in]; w_base [C_out,kh,kw,C_base]; w_cond [C_out,kh,kw,C_in-C_base]
     (None or zero-width for a dense layer).  Every array is widened to float64 exactly.
     groups > 1: channel grouping (output group i uses input group i as base), optionally with the
-    output channels of y stored shuffled."""
+    output channels of y stored shuffled.  tau_c > 0: channel-wise gate (an image's output channel
+    keeps its conditional path only if at least tau_c of its activations fired); out["pre_counts"]
+    holds the sums it thresholds."""
     lib = _load()
     x = _as(x, np.float64)
     w_base = _as(w_base, np.float64)
@@ -138,6 +142,9 @@ def forward_float(x, w_base, w_cond, *, stride=1, pad=1, gate_mean=None, gate_va
     p.is_int, p.out_i8, p.epilogue = 0, 0, epilogue
     p.two_sided = 1 if delta_hi is not None else 0
     p.groups, p.shuffle = int(groups), int(bool(shuffle))
+    p.tau_c = float(tau_c)
+    out["pre_counts"] = np.empty(n * c_out, np.uint32)
+    p.pre_counts = _ptr(out["pre_counts"], _pu32)
     p.gate_eps = gate_eps
     for name in ("x", "w_base", "w_cond", "gate_mean", "gate_var", "delta", "delta_hi",
                  "scale0", "shift0", "scale1", "shift1"):
@@ -160,7 +167,7 @@ def forward_float(x, w_base, w_cond, *, stride=1, pad=1, gate_mean=None, gate_va
 
 def forward_int8(x, w_base, w_cond, thr, *, stride=1, pad=1, out_i8=False, rq_mult0=None, rq_mult1=None,
                  rq_bias=None, rq_shift=0, residual=None, rq_res_mult=0, epilogue=RELU, want_partials=True,
-                 groups=1, shuffle=False):
+                 groups=1, shuffle=False, tau_c=0.0):
     """Integer path: int8 inputs, int32 accumulation, int32 thresholds; exact."""
     lib = _load()
     x = _as(x, np.int8)
@@ -190,6 +197,9 @@ def forward_int8(x, w_base, w_cond, thr, *, stride=1, pad=1, out_i8=False, rq_mu
     p.kh, p.kw, p.stride, p.pad = kh, kw, stride, pad
     p.is_int, p.out_i8, p.epilogue = 1, int(bool(out_i8)), epilogue
     p.groups, p.shuffle = int(groups), int(bool(shuffle))
+    p.tau_c = float(tau_c)
+    out["pre_counts"] = np.empty(n * c_out, np.uint32)
+    p.pre_counts = _ptr(out["pre_counts"], _pu32)
     p.xi, p.wi_base, p.wi_cond = _ptr(x, _pi8), _ptr(w_base, _pi8), _ptr(w_cond, _pi8)
     p.thr = _ptr(thr, _pi32)
     p.rq_mult0, p.rq_mult1, p.rq_bias = _ptr(rq_mult0, _pi32), _ptr(rq_mult1, _pi32), _ptr(rq_bias, _pi32)

@@ -40,6 +40,15 @@
  * of y (and reads the residual there); P, R, d, margin, bitmap and counts keep
  * the natural channel order.
  *
+ * Channel-wise gate (Sec. 3.2, the weight-access extension): with tau_c > 0 an
+ * output channel of an image keeps its conditional path only if at least a
+ * fraction tau_c of its activations fired, S = theta(sum_{pixels} s - tau_c *
+ * wo * ho) with theta(0) = 1; where S = 0 every activation of that channel and
+ * image takes the d = 0 branch of Eq. 1.  d, bitmap, counts, macs and y then
+ * describe the decisions after this gate; pre_counts keeps the sums it
+ * thresholded.  tau_c = 0 switches it off (a sum is never negative).  The paper
+ * defines the sum over one feature map; with a batch it is taken per image.
+ *
  * All tensors are NHWC: x[n][h][w][c_in], outputs [n][ho][wo][c_out].
  * Weights: w_base[c_out][kh][kw][c_base], w_cond[c_out][kh][kw][c_in-c_base].
  */
@@ -63,6 +72,7 @@ typedef struct cg_ref_problem {
   int32_t groups;      /* 0 or 1: x_p = first c_base channels for every output
                           channel; G > 1: channel grouping (Sec. 3.3) */
   int32_t shuffle;     /* grouping only: store y channel-shuffled */
+  double tau_c;        /* channel-wise gate threshold, fraction of ho*wo; 0 = off */
 
   /* float path inputs */
   const double *x, *w_base, *w_cond;
@@ -90,6 +100,8 @@ typedef struct cg_ref_problem {
   uint32_t *counts;       /* [2 + n*c_out]: total (lo,hi), then per (image, channel) */
   uint64_t *macs;         /* multiply-adds on in-range taps: base everywhere,
                              conditional only where the gate fired (Eq. 1) */
+  uint32_t *pre_counts;   /* [n*c_out]: fired activations per (image, channel)
+                             before the channel-wise gate */
 } cg_ref_problem;
 
 static int out_size(int in, int k, int stride, int pad) {
@@ -271,6 +283,55 @@ int cg_ref_forward(const cg_ref_problem *p) {
       }
     }
   }
+  if (p->pre_counts && p->counts)
+    memcpy(p->pre_counts, p->counts + 2, (size_t)N * CO * sizeof(uint32_t));
+
+  /* channel-wise gate: where fewer than tau_c * ho * wo activations of an
+   * (image, channel) fired, all of them fall back to the base path alone */
+  if (gated && p->tau_c > 0.0) {
+    if (!p->d || !p->counts) return 1; /* the pass needs the decisions and their sums */
+    if (p->is_int ? (!p->yi || !p->yi_other) : (!p->y || !p->y_other)) return 1;
+    const double need = p->tau_c * (double)((size_t)HO * WO);
+    for (int n = 0; n < N; ++n) {
+      for (int co = 0; co < CO; ++co) {
+        uint32_t *cnt = &p->counts[2 + (size_t)n * CO + co];
+        if ((double)*cnt >= need) continue; /* S = 1 */
+        const int grp = co / CPG;
+        for (int ho = 0; ho < HO; ++ho) {
+          for (int wo = 0; wo < WO; ++wo) {
+            const size_t m = ((size_t)n * HO + ho) * WO + wo;
+            const size_t o = m * CO + co;
+            if (!p->d[o]) continue;
+            const size_t oy = p->shuffle ? m * CO + (size_t)(co % CPG) * G + grp : o;
+            p->d[o] = 0;
+            if (p->bitmap) p->bitmap[m * words + (co >> 5)] &= ~(1u << (co & 31));
+            if (p->is_int) {
+              const int32_t t = p->yi[oy];
+              p->yi[oy] = p->yi_other[oy];
+              p->yi_other[oy] = t;
+            } else {
+              const double t = p->y[oy];
+              p->y[oy] = p->y_other[oy];
+              p->y_other[oy] = t;
+            }
+            uint64_t taps_in = 0;
+            for (int r = 0; r < KH; ++r) {
+              const int hi = ho * ST - PD + r;
+              if (hi < 0 || hi >= H) continue;
+              for (int s = 0; s < KW; ++s) {
+                const int wi = wo * ST - PD + s;
+                if (wi >= 0 && wi < W) ++taps_in;
+              }
+            }
+            total_macs -= taps_in * (uint64_t)CR;
+            --total_fired;
+          }
+        }
+        *cnt = 0;
+      }
+    }
+  }
+
   if (p->counts) {
     p->counts[0] = (uint32_t)(total_fired & 0xffffffffu);
     p->counts[1] = (uint32_t)(total_fired >> 32);

@@ -405,7 +405,6 @@ int cg_conv_forward(cg_conv* h, int32_t n, const void* x, const void* residual, 
   p.groups = d.groups > 1 ? d.groups : 1;
   p.cpg = d.c_out / p.groups;
   p.shuffle = d.shuffle;
-  p.debug = 0;
   const size_t ts = l.table_stride;
   p.thr_f = (const float*)(pk + 0 * ts);
   p.thr_hi_f = (const float*)(pk + 1 * ts);

@@ -24,7 +24,6 @@ struct Params {
   int groups;              // >= 1; > 1: channel grouping (Sec. 3.3), output group i has input group i as base
   int cpg;                 // output channels per group = c_out / groups
   int shuffle;             // y (and the residual) in shuffled channel order: channel j of group i at j*groups + i
-  int debug;               // profiling knobs (CG_DEBUG_SKIP): results are wrong when non-zero
 
   // per-output-channel tables, device, in `packed`
   const float* thr_f;      // lower threshold on the fp32 base sum (Sec. 3.2 merged gate)

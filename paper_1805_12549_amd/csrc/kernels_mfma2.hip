@@ -154,14 +154,6 @@ __global__ __launch_bounds__(kThreads, 1) void gated_conv_compact_kernel(Params 
   }
   const int total_rows = p.n * p.ho;
   if (tile * g.tr >= total_rows) return;
-  const bool stamp = (p.debug & 16) && p.counts && tid == 0 && (blockIdx.x == 0 || blockIdx.x == gridDim.x / 2 + 1);
-  long long* stamps = (long long*)p.counts + (blockIdx.x == 0 ? 1 : 17);
-  int n_stamp = 0;
-#define CG_STAMP()                                  \
-  do {                                              \
-    if (stamp) stamps[n_stamp++] = clock64();       \
-  } while (0)
-  CG_STAMP();
   const int R0 = tile * g.tr;
   const int img0 = fdiv(R0, g.magic_ho);
   const int base0 = img0 * g.hp + (R0 - img0 * p.ho) * p.stride;   // stacked padded input row of patch row 0
@@ -199,7 +191,6 @@ __global__ __launch_bounds__(kThreads, 1) void gated_conv_compact_kernel(Params 
   }
   for (int i = tid; i < g.max_imgs * kBN; i += kThreads) colcnt[i] = 0u;
   __syncthreads();
-  CG_STAMP();
 
   // ---- this thread's load slots: slot ci = k*threads + tid of the patch is (chunk plane ci / nps,
   // pixel ci % nps); nps slots per plane, the ones past npix stay zero
@@ -242,14 +233,14 @@ __global__ __launch_bounds__(kThreads, 1) void gated_conv_compact_kernel(Params 
     const int ss = ph ? s - S0 : s;
     char* wdst = pdst + g.patch_bytes;
     const char* ws = (ph ? wpk1 : wpk0) + ((size_t)cbk * g.stages[ph] + ss) * g.wpk_stage_bytes;
-    if (t < WROWS && !(p.debug & 64)) {
+    if (t < WROWS) {
       if (t * kThreads + tid < T * 256)
         lds_direct_16(ws + (t * kThreads + tid) * 16, wdst + (t * kThreads + wave * 64) * 16);
     }
     const char* xs = xbytes + (long long)((ph ? p.c_base : 0) + ss * CBQ * g.ch) * eb;
 #pragma unroll
     for (int k = 0; k < kKP; ++k) {
-      if (k % T == t && k < g.kp && !(p.debug & 32)) {
+      if (k % T == t && k < g.kp) {
         if (gsl[k] >= 0) lds_direct_16(xs + gsl[k], pdst + (k * kThreads + wave * 64) * 16);
       }
     }
@@ -322,34 +313,26 @@ __global__ __launch_bounds__(kThreads, 1) void gated_conv_compact_kernel(Params 
     }
   }
 
-  CG_STAMP();
   issue_stage(0, bufA);
   __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): the LDS-direct loads have landed
   __syncthreads();
-  CG_STAMP();
 
   // one K stage: prefetch the next stage into `nxt`, multiply out of `cur`
   auto do_stage = [&](int s, const char* cur, char* nxt) __attribute__((always_inline)) {
-    const bool prefetch = s + 1 < S && !(p.debug & 2);
+    const bool prefetch = s + 1 < S;
     auto part = [&](int t) __attribute__((always_inline)) {
       if (prefetch) issue_part(s + 1, nxt, t);
     };
-    if (s == 1) CG_STAMP();
     const char* patch = cur;
     const char* wb = cur + g.patch_bytes + wlane;
-    if (p.debug & 1) {
-#pragma unroll
-      for (int t = 0; t < T; ++t) part(t);
-    } else if (s < S0) {
+    if (s < S0) {
       // every wavefront multiplies NGW groups: the ones past the tile's end read pixel 0 and are dropped
       mma_stage<Tr, CBQ, NGW, NGW>(patch, wb, arow, aoff, zaddr, accP, part);
     } else {
       mma_dispatch<Tr, CBQ, NGW>(nr_wg, patch, wb, arow_c, aoff, zaddr, accR, part);
     }
-    if (s == 1) CG_STAMP();
 
     if (s == S0 - 1 && p.gated) {
-      CG_STAMP();
       // ---- gate ------------------------------------------------------------------------------
       // images (relative to img0) of this wavefront's first and last live pixel
       int last_row = (wave * NGW + ngrp) * 16 - 1;
@@ -420,9 +403,7 @@ __global__ __launch_bounds__(kThreads, 1) void gated_conv_compact_kernel(Params 
           }
         }
       }
-      CG_STAMP();
       __syncthreads();
-      CG_STAMP();
 
       // ---- compaction: every wavefront scans all flags, thread r places row r ----------------------
       int n_act = 0, my_prefix = 0;
@@ -453,12 +434,10 @@ __global__ __launch_bounds__(kThreads, 1) void gated_conv_compact_kernel(Params 
         arow_c[fr] = out_pp[c < n_act ? clist[c] : 0] * 16 + q * g.pln;
       }
       if (n_act == 0) S = s + 1;   // nothing fired in this tile: the conditional stages are skipped
-      CG_STAMP();
     }
 
     __builtin_amdgcn_s_waitcnt(0x0F70);
     __syncthreads();
-    if (s == 1) CG_STAMP();
   };
 
   for (int s = 0; s < S; s += 2) {
@@ -466,7 +445,6 @@ __global__ __launch_bounds__(kThreads, 1) void gated_conv_compact_kernel(Params 
     if (s + 1 < S) do_stage(s + 1, bufB, bufA);
   }
 
-  CG_STAMP();
   // ---- output: P by tile row, R by compacted row, both through LDS ---------------------------------
   acc_t* tileP = (acc_t*)bufA;
   acc_t* tileR = (acc_t*)bufB;
@@ -496,8 +474,7 @@ __global__ __launch_bounds__(kThreads, 1) void gated_conv_compact_kernel(Params 
   }
   __syncthreads();
 
-  CG_STAMP();
-  const int rows_used = (p.debug & 4) ? 0 : g.ng * 16;
+  const int rows_used = g.ng * 16;
 #pragma unroll 4
   for (int idx = tid; idx < rows_used * 8; idx += kThreads) {
     const int row = idx >> 3, c8 = idx & 7;
@@ -532,7 +509,6 @@ __global__ __launch_bounds__(kThreads, 1) void gated_conv_compact_kernel(Params 
     finish_store8<Tr>(p, s0, s1, db, co0, o);
   }
 
-  CG_STAMP();
   if (p.bitmap) {
     for (int idx = tid; idx < rows_used * 2; idx += kThreads) {
       const int row = idx >> 1, w = idx & 1;
@@ -540,7 +516,7 @@ __global__ __launch_bounds__(kThreads, 1) void gated_conv_compact_kernel(Params 
       if (m >= 0) p.bitmap[(long long)m * p.words + cbk * 2 + w] = dbits[idx];
     }
   }
-  if (p.counts && p.gated && !(p.debug & 16)) {
+  if (p.counts && p.gated) {
     unsigned long long mine = 0;
     for (int idx = tid; idx < g.max_imgs * kBN; idx += kThreads) {
       const int il = idx >> 6, c = idx & 63;
@@ -555,7 +531,6 @@ __global__ __launch_bounds__(kThreads, 1) void gated_conv_compact_kernel(Params 
     for (int sft = 32; sft >= 1; sft >>= 1) mine += (unsigned)shfl_xor_i((int)(unsigned)(mine & 0xffffffffu), sft);
     if (lane == 0 && mine) atomicAdd((unsigned long long*)p.counts, mine);
   }
-#undef CG_STAMP
 }
 
 template <typename Tr, int NGW, int CBQ>

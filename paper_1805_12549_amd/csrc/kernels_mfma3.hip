@@ -179,7 +179,7 @@ __device__ __forceinline__ void mma_granule(const char* __restrict__ pat, const 
 }
 
 template <typename Tr, int NF, int CPS, int PKB, int NWV>
-__global__ __launch_bounds__(NWV * 64, PKB == 12 ? 3 : 2) void gated_conv_rows_kernel(
+__global__ __launch_bounds__(NWV * 64, 2) void gated_conv_rows_kernel(
     Params p, Mfma3Plan g, const char* __restrict__ wpk0, const char* __restrict__ wpk1) {
   using acc16 = typename Tr::acc16;
   using acc_t = typename Tr::acc_t;
@@ -817,9 +817,6 @@ hipError_t launch_rows_one(const Mfma3Plan& g, const Params& p, const void* w0, 
 
 template <typename Tr, int NF, int CPS>
 hipError_t launch_rows_cps(const Mfma3Plan& g, const Params& p, const void* w0, const void* w1, hipStream_t s) {
-  if constexpr (NF == 1) {
-    if (g.pkb == 12) return launch_rows_one<Tr, NF, CPS, 12, 4>(g, p, w0, w1, s);
-  }
   if (g.pkb == 24) return launch_rows_one<Tr, NF, CPS, 24, 4>(g, p, w0, w1, s);
   return launch_rows_one<Tr, NF, CPS, 48, 4>(g, p, w0, w1, s);
 }
@@ -871,8 +868,6 @@ Mfma3Plan mfma3_plan(const cg_conv_desc& d) {
     g.cps = 2;
   else
     return g;
-  const char* env_cps = getenv("CG_MFMA3_CPS");
-  if (env_cps && atoi(env_cps) == 2) g.cps = 2;
   if (d.c_out % kBn) return g;
   const int ho = (d.h + 2 * d.pad - 3) / d.stride + 1, wo = (d.w + 2 * d.pad - 3) / d.stride + 1;
   // 32-bit byte offsets and 16-bit row numbers inside the kernel
@@ -891,9 +886,6 @@ Mfma3Plan mfma3_plan(const cg_conv_desc& d) {
   const int P = 1 << g.logp;
   const int sb = 16 * g.cps;
   const long long rows = (long long)d.n_max * ho;
-  const char* env_nf = getenv("CG_MFMA3_NF");
-  const char* env_pkb = getenv("CG_MFMA3_PKB");
-  const char* env_nwv = getenv("CG_MFMA3_NWV");
   auto gcd = [](int a, int b) {
     while (b) {
       const int t = a % b;
@@ -922,13 +914,9 @@ Mfma3Plan mfma3_plan(const cg_conv_desc& d) {
     int nwv, pkb;
     long long min_wg;
   };
-  const Cand cands[] = {{4, 12, 0}, {4, 24, 0}, {4, 48, 0}};
-  (void)env_nwv;
+  const Cand cands[] = {{4, 24, 0}, {4, 48, 0}};
   for (const Cand& c : cands) {
-    if (env_pkb ? atoi(env_pkb) != c.pkb : c.pkb == 12) continue;   // the 12 KB class only on request
     for (int nf = 2; nf >= 1; --nf) {
-      if (env_nf && atoi(env_nf) != nf) continue;
-      if (c.pkb == 12 && nf == 2) continue;
       const int bm = 32 * nf * c.nwv;
       int tr = bm / wo;
       if (tr < 1) continue;
@@ -938,7 +926,7 @@ Mfma3Plan mfma3_plan(const cg_conv_desc& d) {
       if (t < 1 || 4 * t < 3 * tr) continue;
       const long long tiles = (rows + t - 1) / t;
       if (tiles * g.n_cb < c.min_wg) continue;
-      if (c.nwv == 4 && nf == 2 && !env_nf && tiles * g.n_cb < 256) continue;
+      if (nf == 2 && tiles * g.n_cb < 256) continue;   // the large tile only when it still fills the CUs
       g.nwv = c.nwv;
       g.nf = nf;
       g.bm = bm;

@@ -7,12 +7,14 @@ Follows Eq. 1 and the merged gate of Sec. 3.2 of the channel-gating paper.
 from fractions import Fraction
 
 
-def gated_conv_brute(x, w_base, w_cond, stride, pad, thr, exact=True, groups=1):
+def gated_conv_brute(x, w_base, w_cond, stride, pad, thr, exact=True, groups=1, tau_c=0):
     """x: nested list [N][H][W][C]; w_base [CO][KH][KW][CP]; w_cond [CO][KH][KW][CR];
     thr: per-channel threshold on the raw partial sum (gate fires iff P >= thr[co]).
     groups > 1 (Sec. 3.3): the output channels are cut into `groups` equal runs; run i reads
     input channels [i*CP, (i+1)*CP) on the base path and all the others, in order, on the
     conditional path.
+    tau_c > 0 (channel-wise gate of Sec. 3.2): an output channel of an image whose fired count is
+    below tau_c * HO * WO loses its conditional path altogether.
     Returns P, R, d, S as nested lists [N][HO][WO][CO] (Fractions if exact)."""
     conv = Fraction if exact else (lambda v: v)
     N, H, W = len(x), len(x[0]), len(x[0][0])
@@ -49,4 +51,13 @@ def gated_conv_brute(x, w_base, w_cond, stride, pad, thr, exact=True, groups=1):
                     R[n][oh][ow][co] = q
                     D[n][oh][ow][co] = fire if CR else 0
                     S[n][oh][ow][co] = p + q if fire else p
+    if tau_c and CR:
+        for n in range(N):
+            for co in range(CO):
+                fired = sum(D[n][oh][ow][co] for oh in range(HO) for ow in range(WO))
+                if fired < Fraction(tau_c) * HO * WO:
+                    for oh in range(HO):
+                        for ow in range(WO):
+                            D[n][oh][ow][co] = 0
+                            S[n][oh][ow][co] = P[n][oh][ow][co]
     return P, R, D, S

@@ -74,6 +74,13 @@ def test_valid_descriptor_sizes_packed_buffer():
     (dict(w_cond=None), B.CG_EINVAL),
     (dict(h=1, w=1, pad=0), B.CG_EINVAL),
     (dict(in_dtype=B.CG_F32, variant=B.CG_VARIANT_MFMA), B.CG_EUNSUPPORTED),
+    (dict(groups=-1), B.CG_EINVAL),
+    (dict(groups=2), B.CG_EINVAL),                      # c_base * groups != c_in
+    (dict(groups=4, c_out=30), B.CG_EINVAL),            # groups does not divide c_out
+    (dict(shuffle=1), B.CG_EINVAL),                     # shuffle without grouping
+    (dict(groups=4, shuffle=2), B.CG_EINVAL),
+    (dict(groups=4, variant=B.CG_VARIANT_MFMA), B.CG_EUNSUPPORTED),
+    (dict(groups=4, variant=B.CG_VARIANT_MFMA_COMPACT), B.CG_EUNSUPPORTED),
 ])
 def test_invalid_descriptors_are_rejected_without_a_gpu(over, code):
     d = make_desc(**over)
@@ -83,6 +90,12 @@ def test_invalid_descriptors_are_rejected_without_a_gpu(over, code):
     assert rc == code, B.cg_last_error()
     assert h.value is None
     assert len(B.cg_last_error()) > 0
+
+
+def test_grouped_descriptor_is_accepted():
+    assert B.cg_conv_packed_bytes(make_desc(groups=4)) > 0
+    assert B.cg_conv_packed_bytes(make_desc(groups=4, shuffle=1)) > 0
+    assert B.cg_conv_packed_bytes(make_desc(groups=1)) == B.cg_conv_packed_bytes(make_desc())
 
 
 def test_missing_gate_statistics_and_nan():

@@ -500,3 +500,99 @@ def test_grouped_rejects_bad_problems():
         O.forward_float(x, np.ones((4, 3, 3, 2)), np.ones((4, 3, 3, 4)), groups=3, **st)
     with pytest.raises(ValueError):   # shuffle without grouping
         O.forward_float(x, np.ones((4, 3, 3, 2)), np.ones((4, 3, 3, 4)), shuffle=True, **st)
+
+
+# ---------------------------------------------------------------------------
+# Channel-wise gate (Sec. 3.2): an output channel of an image keeps its conditional path only if
+# at least a fraction tau_c of its activations fired
+# ---------------------------------------------------------------------------
+@pytest.mark.parametrize("tau", [Fraction(1, 10), Fraction(3, 10), Fraction(1, 2), Fraction(9, 10)])
+@pytest.mark.parametrize("g,stride", [(1, 1), (2, 2)])
+def test_channel_gate_brute_force(tau, g, stride):
+    rng = np.random.default_rng(1200 + g + tau.numerator)
+    n, h, w, c_in, c_out = 3, 6, 5, 8, 6
+    x = rng.integers(0, 6, (n, h, w, c_in)).astype(np.float64)
+    wfull = rng.integers(-3, 4, (c_out, 3, 3, c_in)).astype(np.float64)
+    if g > 1:
+        wb, wc = split_grouped(wfull, g)
+    else:
+        wb, wc = np.ascontiguousarray(wfull[..., :2]), np.ascontiguousarray(wfull[..., 2:])
+    thr = rng.integers(-4, 12, c_out).astype(np.float64)
+    out = O.forward_float(x, wb, wc, stride=stride, pad=1, gate_mean=np.zeros(c_out), gate_var=np.ones(c_out),
+                          delta=thr, epilogue=0, groups=g, tau_c=float(tau))
+    P, R, D, S = gated_conv_brute(x.tolist(), wb.tolist(), wc.tolist(), stride, 1, [Fraction(int(t)) for t in thr],
+                                  groups=g, tau_c=tau)
+    D = np.array(D, dtype=np.uint8)
+    assert np.array_equal(out["d"], D)
+    np.testing.assert_array_equal(out["y"], np.array(S, dtype=np.float64))
+    # the test means something only if the gate removed some channels and kept others
+    pre = out["pre_counts"].reshape(n, c_out)
+    post = out["counts"][2:].reshape(n, c_out)
+    assert np.array_equal(post, D.sum(axis=(1, 2)))
+    if tau >= Fraction(3, 10):
+        assert ((post == 0) & (pre > 0)).any()
+    if tau <= Fraction(1, 2):
+        assert (post > 0).any()
+    assert out["fired"] == int(D.sum()) == sum(bin(int(v)).count("1") for v in out["bitmap"].reshape(-1))
+    # integer path on the same numbers
+    oi = O.forward_int8(x.astype(np.int8), wb.astype(np.int8), wc.astype(np.int8), thr.astype(np.int32),
+                        stride=stride, pad=1, epilogue=0, groups=g, tau_c=float(tau))
+    assert np.array_equal(oi["d"], D) and np.array_equal(oi["y"], np.array(S, dtype=np.int64))
+
+
+def test_channel_gate_painted_counts_and_tie():
+    """A one-hot centre tap makes P a copy of an input channel, so the fired count of each output
+    channel is painted by hand: channel 0 fires on 12 of 30 pixels, channel 1 on 29, channel 2 on 30."""
+    h, w = 5, 6
+    x = np.zeros((2, h, w, 4))
+    x[0, :2, :, 0] = 5.0          # image 0, channel 0: the first two rows (12 pixels)
+    x[0, :, :, 1] = 5.0
+    x[0, 0, 0, 1] = 0.0           # channel 1: everything but one pixel (29)
+    x[:, :, :, 2] = 5.0           # channel 2: everywhere, both images
+    x[1, 2, 3, 0] = 5.0           # image 1, channel 0: a single pixel
+    x[..., 3] = 1.0               # the conditional channel
+    wb = np.zeros((3, 3, 3, 3))
+    wb[np.arange(3), 1, 1, np.arange(3)] = 1.0
+    wc = np.zeros((3, 3, 3, 1))
+    wc[:, 1, 1, 0] = 100.0        # R = 100 wherever computed
+    kw = dict(gate_mean=np.zeros(3), gate_var=np.ones(3), delta=np.full(3, 1.0), epilogue=0)
+    base = O.forward_float(x, wb, wc, **kw)
+    assert base["counts"][2:].tolist() == [12, 29, 30, 1, 0, 30]
+    tie = O.forward_float(x, wb, wc, tau_c=0.4, **kw)          # 0.4 * 30 = 12: equality keeps the channel
+    assert tie["counts"][2:].tolist() == [12, 29, 30, 0, 0, 30]
+    assert tie["pre_counts"].tolist() == [12, 29, 30, 1, 0, 30]
+    over = O.forward_float(x, wb, wc, tau_c=0.41, **kw)
+    assert over["counts"][2:].tolist() == [0, 29, 30, 0, 0, 30]
+    np.testing.assert_array_equal(over["y"][0, :, :, 0], x[0, :, :, 0])          # base path only: y = P
+    np.testing.assert_array_equal(over["y"][0, :, :, 1], x[0, :, :, 1] + 100.0 * (x[0, :, :, 1] >= 1))
+    full = O.forward_float(x, wb, wc, tau_c=1.0, **kw)          # only all-firing channels survive
+    assert full["counts"][2:].tolist() == [0, 0, 30, 0, 0, 30]
+    assert full["fired"] == 60 and full["macs"] < over["macs"] < tie["macs"] < base["macs"]
+    none = O.forward_float(x, wb, wc, tau_c=1.01, **kw)
+    assert none["fired"] == 0 and not none["bitmap"].any()
+    np.testing.assert_array_equal(none["y"], base["P"])
+
+
+def test_channel_gate_extremes_and_nesting():
+    rng = np.random.default_rng(55)
+    n, c_in, c_out, g = 3, 12, 8, 4
+    x, wb, wc = rand_problem(rng, n, 9, 7, c_in, c_out, g)
+    mean, var = np.zeros(c_out), np.ones(c_out)
+    kw = dict(stride=1, pad=1, gate_mean=mean, gate_var=var, delta=rng.uniform(0.2, 1.5, c_out), epilogue=O.RELU)
+    off = O.forward_float(x, wb, wc, **kw)
+    zero = O.forward_float(x, wb, wc, tau_c=0.0, **kw)
+    np.testing.assert_array_equal(off["y"], zero["y"])
+    assert np.array_equal(off["d"], zero["d"]) and off["macs"] == zero["macs"]
+    never = O.forward_float(x, wb, wc, tau_c=2.0, **kw)
+    np.testing.assert_allclose(never["y"], np.maximum(lib_conv(x[..., : c_in // g], wb, 1, 1), 0), rtol=1e-12, atol=1e-12)
+    prev = off["d"]
+    sums = []
+    for tau in (0.1, 0.2, 0.3, 0.5, 0.8):
+        cur = O.forward_float(x, wb, wc, tau_c=tau, **kw)
+        assert not (cur["d"] & ~prev).any()                         # decisions only ever drop out
+        pre = cur["pre_counts"].reshape(n, c_out)
+        keep = pre >= tau * 9 * 7
+        assert np.array_equal(cur["d"], off["d"] * keep[:, None, None, :])
+        prev = cur["d"]
+        sums.append(int(prev.sum()))
+    assert any(0 < v < int(off["d"].sum()) for v in sums)
