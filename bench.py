@@ -45,6 +45,9 @@ def parse():
     ap.add_argument("--grouped", action="store_true",
                     help="channel grouping (output group i takes input group i as its base path) instead of the "
                          "default fixed base channels")
+    ap.add_argument("--tau-c", type=float, default=0.0,
+                    help="channel-wise gate: an image's output channel keeps its conditional path only if at "
+                         "least this fraction of its activations fired (0 = off)")
     ap.add_argument("--layers", default="", help="comma-separated layer names to restrict the workload")
     return ap.parse_args()
 
@@ -90,7 +93,7 @@ def main():
         common = dict(n_max=s.n, h=s.h, w=s.w, c_in=s.c_in, c_out=s.c_out, in_dtype=B.CG_BF16, out_dtype=B.CG_BF16,
                       stride=s.stride, pad=s.pad, epilogue=B.CG_EPI_RELU, variant=variant)
         gated = B.GatedConv(c_base=s.c_base, w_base=wb, w_cond=wc, gate_mean=gate.mean, gate_var=gate.var,
-                            delta=gate.delta, groups=s.groups if args.grouped else 0, **common)
+                            delta=gate.delta, groups=s.groups if args.grouped else 0, tau_c=args.tau_c, **common)
         dense = None if args.no_dense else B.GatedConv(c_base=s.c_in, w_base=wfull, w_cond=None, **common)
         layers.append(dict(shape=s, inp=inp, gate=gate, xs=xs, ys=ys, bms=bms, gated=gated, dense=dense, nset=nset))
     torch.cuda.synchronize()
@@ -197,6 +200,7 @@ def main():
     traffic = None     # measured HBM bytes per launch, from the committed counter summary
     tfile = ROOT / "profiles" / "hbm_traffic_gated_conv_rows_kernel_imagenet_resnet18_bf16_n64.txt"
     if (tfile.exists() and args.batch == 64 and not args.layers and args.kind == "coherent" and not args.grouped
+            and args.tau_c == 0.0
             and layers[0]["gated"].variant == B.CG_VARIANT_MFMA_ROWS):
         m = re.search(r"^bytes_per_launch:\s*(\d+)", tfile.read_text(), re.M)
         traffic = int(m.group(1)) if m else None
@@ -223,7 +227,7 @@ def main():
             tc = time.perf_counter()
             O.forward_float(x64, wb64, wc64, stride=s.stride, pad=s.pad, gate_mean=gate.mean, gate_var=gate.var,
                             delta=gate.delta, epilogue=O.RELU, want_partials=False,
-                            groups=s.groups if args.grouped else 1)
+                            groups=s.groups if args.grouped else 1, tau_c=float(np.float32(args.tau_c)))
             t_cpu += time.perf_counter() - tc
             ops_cpu += 2 * s.dense_macs
         cores = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
@@ -252,7 +256,8 @@ def main():
         "config": {"workload": "ImageNet-shaped ResNet-18 gated 3x3 convs (configs[2]): batch %d, bf16 NHWC, G=4, "
                                "%s gate maps, target firing %.2f%s; step = all %d layers" %
                                (args.batch, args.kind, args.rho,
-                                ", channel grouping" if args.grouped else "", len(layers)),
+                                (", channel grouping" if args.grouped else "") +
+                                (", channel-wise gate tau_c=%.2f" % args.tau_c if args.tau_c > 0 else ""), len(layers)),
                    "launch": "hip graph replay" if graph is not None else "eager",
                    "sum_us_gated": round(t_kernel_us, 2),
                    "sum_us_dense": None if args.no_dense else round(sum(L["us_dense"] for L in layers), 2),

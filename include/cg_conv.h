@@ -112,6 +112,14 @@ typedef struct cg_conv_desc {
   int32_t rq_shift;          /* 0..31 */
   int32_t rq_res_mult;
 
+  /* Channel-wise gate (Sec. 3.2, the weight-access extension): with tau_c > 0 an output channel of
+   * an image keeps its conditional path only if at least tau_c * Ho * Wo of its activations fired
+   * (equality keeps it); otherwise every activation of that channel and image takes the d = 0
+   * branch.  y, bitmap and counts then describe the decisions after this gate.  0 = off.
+   * Costs a second pass over the base path (the sums must be complete before any conditional work). */
+  float tau_c;
+  int32_t reserved0;
+
   void* packed;              /* DEVICE, >= cg_conv_packed_bytes(desc), 256-byte aligned, caller-owned;
                                 must outlive the handle; holds repacked weights and per-channel tables */
   size_t packed_bytes;

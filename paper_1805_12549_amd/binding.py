@@ -70,6 +70,7 @@ class cg_conv_desc(C.Structure):
         ("scale0", _pf), ("shift0", _pf), ("scale1", _pf), ("shift1", _pf),
         ("rq_mult0", _pi), ("rq_mult1", _pi), ("rq_bias", _pi),
         ("rq_shift", C.c_int32), ("rq_res_mult", C.c_int32),
+        ("tau_c", C.c_float), ("reserved0", C.c_int32),
         ("packed", C.c_void_p), ("packed_bytes", C.c_size_t),
     ]
 
@@ -165,7 +166,8 @@ class GatedConv:
 
     w_base / w_cond: torch device tensors [C_out,kh,kw,C_base] / [C_out,kh,kw,C_in-C_base] in the
     input dtype (bf16 tensors for CG_BF16, int8 for CG_I8, float32 for CG_F32).
-    groups > 1 selects channel grouping, shuffle the channel-shuffled store (see cg_conv.h).
+    groups > 1 selects channel grouping, shuffle the channel-shuffled store, tau_c > 0 the
+    channel-wise gate (see cg_conv.h).
     """
 
     def __init__(self, *, n_max, h, w, c_in, c_out, c_base, w_base, w_cond, in_dtype, out_dtype,
@@ -173,7 +175,7 @@ class GatedConv:
                  gate_mean=None, gate_var=None, delta=None, delta_hi=None, gate_eps=0.0, gate_thr_i32=None,
                  scale0=None, shift0=None, scale1=None, shift1=None,
                  rq_mult0=None, rq_mult1=None, rq_bias=None, rq_shift=0, rq_res_mult=0,
-                 x_pixel_stride=0, groups=0, shuffle=False, stream=None):
+                 x_pixel_stride=0, groups=0, shuffle=False, tau_c=0.0, stream=None):
         import torch
         self._torch = torch
         self.handle = None
@@ -184,6 +186,7 @@ class GatedConv:
         d.in_dtype, d.out_dtype, d.epilogue, d.variant = in_dtype, out_dtype, epilogue, variant
         d.x_pixel_stride = x_pixel_stride
         d.groups, d.shuffle = int(groups), int(bool(shuffle))
+        d.tau_c = float(tau_c)
         self._keep = [w_base, w_cond]
         d.w_base = w_base.data_ptr()
         d.w_cond = w_cond.data_ptr() if (w_cond is not None and w_cond.numel()) else None

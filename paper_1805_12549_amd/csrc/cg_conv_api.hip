@@ -86,6 +86,7 @@ int validate(const cg_conv_desc* d, int* ho, int* wo) {
   }
   if (d->shuffle != 0 && d->shuffle != 1) return fail(CG_EINVAL, "shuffle must be 0 or 1");
   if (d->shuffle && d->groups <= 1) return fail(CG_EINVAL, "shuffle needs channel grouping (groups > 1)");
+  if (!(d->tau_c >= 0.0f) || std::isinf(d->tau_c)) return fail(CG_EINVAL, "tau_c must be finite and >= 0");
   if (d->in_dtype != CG_F32 && d->in_dtype != CG_BF16 && d->in_dtype != CG_I8)
     return fail(CG_EINVAL, "in_dtype must be CG_F32, CG_BF16 or CG_I8");
   if (d->in_dtype == CG_I8) {
@@ -344,13 +345,35 @@ int cg_conv_create(cg_conv** out, const cg_conv_desc* desc, void* hip_stream) {
   return CG_OK;
 }
 
+namespace {
+// Workspace layout: [decision bitmap of the batch][per-(image, channel) counts of the first pass]
+// [channel mask].  The row-tiled kernel counts fired gates from a decision bitmap; it goes to the
+// workspace when the caller asks for counts without a bitmap, and so does the first pass of the
+// channel-wise gate.  The other two areas exist only with the channel-wise gate.
+struct WsLayout {
+  size_t bitmap_off, bitmap_bytes, counts_off, counts_bytes, mask_off, mask_bytes, total;
+};
+WsLayout ws_layout(const cg_conv* h, int32_t n) {
+  WsLayout w{};
+  const size_t words = (size_t)(h->d.c_out + 31) / 32;
+  const bool chan_gate = h->c_cond > 0 && h->d.tau_c > 0.0f;
+  if (h->variant == CG_VARIANT_MFMA_ROWS && h->c_cond > 0)
+    w.bitmap_bytes = align256((size_t)n * h->ho * h->wo * words * 4);
+  if (chan_gate) {
+    w.counts_bytes = align256((2 + (size_t)n * h->d.c_out) * 4);
+    w.mask_bytes = align256((size_t)n * words * 4);
+  }
+  w.bitmap_off = 0;
+  w.counts_off = w.bitmap_bytes;
+  w.mask_off = w.counts_off + w.counts_bytes;
+  w.total = w.mask_off + w.mask_bytes;
+  return w;
+}
+}  // namespace
+
 size_t cg_conv_workspace_bytes(const cg_conv* h, int32_t n) {
   if (!h || n <= 0) return 0;
-  // the row-tiled kernel counts fired gates from the decision bitmap; when the caller asks for
-  // counts without a bitmap the bitmap is written to the workspace
-  if (h->variant == CG_VARIANT_MFMA_ROWS && h->c_cond > 0)
-    return align256((size_t)n * h->ho * h->wo * ((h->d.c_out + 31) / 32) * 4);
-  return 0;
+  return ws_layout(h, n).total;
 }
 
 int cg_conv_info(const cg_conv* h, int32_t* ho, int32_t* wo) {
@@ -375,6 +398,7 @@ int cg_conv_forward(cg_conv* h, int32_t n, const void* x, const void* residual, 
   const size_t need = cg_conv_workspace_bytes(h, n);
   if (need > 0 && (!workspace || workspace_bytes < need))
     return fail(CG_EINVAL, "workspace of %zu bytes is smaller than the %zu required", workspace_bytes, need);
+  if (need > 0 && ((uintptr_t)workspace & 255)) return fail(CG_EINVAL, "workspace must be 256-byte aligned");
 
   const cg_conv_desc& d = h->d;
   const char* pk = (const char*)d.packed;
@@ -426,13 +450,41 @@ int cg_conv_forward(cg_conv* h, int32_t n, const void* x, const void* residual, 
 
   hipStream_t s = (hipStream_t)hip_stream;
   hipError_t e = hipSuccess;
-  if (counts) e = cg::launch_zero_u32(counts, 2 + (size_t)n * d.c_out, s);
+  const WsLayout wl = ws_layout(h, n);
+  char* ws = (char*)workspace;
+  if (p.gated && d.tau_c > 0.0f) {
+    // Channel-wise gate (Sec. 3.2): a first pass over the base path and the gate gives the fired
+    // count of every (image, channel); the channels at or above tau_c * Ho * Wo form the mask that
+    // the full pass ANDs into its decisions.
+    const double need_d = std::ceil((double)d.tau_c * (double)((long long)h->ho * h->wo));
+    const uint32_t need_u = need_d >= 4294967295.0 ? 0xffffffffu : (uint32_t)need_d;
+    uint32_t* pre_counts = (uint32_t*)(ws + wl.counts_off);
+    uint32_t* mask = (uint32_t*)(ws + wl.mask_off);
+    cg::Params q = p;
+    q.gate_only = 1;
+    q.y = nullptr;
+    q.counts = nullptr;
+    q.bitmap = nullptr;
+    e = cg::launch_zero_u32(pre_counts, 2 + (size_t)n * d.c_out, s);
+    if (e == hipSuccess && h->variant == CG_VARIANT_MFMA_ROWS) {
+      q.bitmap = (uint32_t*)(ws + wl.bitmap_off);
+      e = cg::launch_mfma3(h->plan3, q, pk + l.wpk_base_off, pk + l.wpk_cond_off, s);
+      q.counts = pre_counts;
+      if (e == hipSuccess) e = cg::launch_bitmap_counts(q, q.bitmap, s);
+    } else if (e == hipSuccess) {
+      q.counts = pre_counts;
+      e = cg::launch_naive(q, s);
+    }
+    if (e == hipSuccess) e = cg::launch_chan_mask(pre_counts, n, d.c_out, p.words, need_u, mask, s);
+    p.chan_mask = mask;
+  }
+  if (e == hipSuccess && counts) e = cg::launch_zero_u32(counts, 2 + (size_t)n * d.c_out, s);
   if (e == hipSuccess && h->variant == CG_VARIANT_MFMA_ROWS) {
     const size_t bm_words = (size_t)p.m_total * p.words;
     if (!p.gated) {
       if (bitmap) e = cg::launch_zero_u32(bitmap, bm_words, s);   // a dense layer has no decisions
     } else if (counts && !bitmap) {
-      p.bitmap = (uint32_t*)workspace;
+      p.bitmap = (uint32_t*)(ws + wl.bitmap_off);   // free again once the mask exists
     }
     if (e == hipSuccess) e = cg::launch_mfma3(h->plan3, p, pk + l.wpk_base_off, pk + l.wpk_cond_off, s);
     if (e == hipSuccess && counts && p.gated) e = cg::launch_bitmap_counts(p, p.bitmap, s);

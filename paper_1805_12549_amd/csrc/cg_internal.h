@@ -24,6 +24,10 @@ struct Params {
   int groups;              // >= 1; > 1: channel grouping (Sec. 3.3), output group i has input group i as base
   int cpg;                 // output channels per group = c_out / groups
   int shuffle;             // y (and the residual) in shuffled channel order: channel j of group i at j*groups + i
+  int gate_only;           // first pass of the channel-wise gate: base path and gate only; writes the bitmap
+                           // (row-tiled kernel) or the per-(image, channel) counts (plain kernel), nothing else
+  const uint32_t* chan_mask;  // second pass: [n][words] bits of the channels that keep their conditional
+                              // path (Sec. 3.2 channel-wise gate), ANDed into the decisions; or NULL
 
   // per-output-channel tables, device, in `packed`
   const float* thr_f;      // lower threshold on the fp32 base sum (Sec. 3.2 merged gate)
@@ -147,6 +151,10 @@ hipError_t launch_mfma3(const Mfma3Plan& plan, const Params& p, const void* wpk_
                         hipStream_t s);
 // per-(image, channel) fired counts and their total (into p.counts, total pre-zeroed) from a decision bitmap
 hipError_t launch_bitmap_counts(const Params& p, const uint32_t* bitmap, hipStream_t s);
+
+// channel-wise gate: mask[img][w] bit b = counts[2 + img*c_out + 32*w + b] >= need
+hipError_t launch_chan_mask(const uint32_t* counts, int n, int c_out, int words, uint32_t need, uint32_t* mask,
+                            hipStream_t s);
 
 // launchers (return hipError_t from the last launch)
 hipError_t launch_naive(const Params& p, hipStream_t s);

@@ -566,7 +566,7 @@ Mfma2Plan mfma2_plan(const cg_conv_desc& d) {
   Mfma2Plan g{};
   g.ok = 0;
   if (d.in_dtype != CG_BF16 && d.in_dtype != CG_I8) return g;
-  if (d.groups > 1) return g;   // channel grouping: row-tiled and plain kernels only
+  if (d.groups > 1 || d.tau_c > 0.0f) return g;   // channel grouping, channel-wise gate: row-tiled and plain kernels only
   if (d.kh != 3 || d.kw != 3) return g;
   g.elem_bytes = d.in_dtype == CG_BF16 ? 2 : 1;
   g.ch = 16 / g.elem_bytes;

@@ -225,7 +225,7 @@ __global__ __launch_bounds__(NWV * 64, 2) void gated_conv_rows_kernel(
   if (R0 >= total_rows) return;
 
   const int S0 = g.stages[0];                       // super-stages of the base phase
-  const int S = S0 + (p.gated ? g.stages[1] : 0);
+  const int S = S0 + ((p.gated && !p.gate_only) ? g.stages[1] : 0);   // a gate-only pass stops after the base phase
   const int G = 3 * S;                              // weight granules
   const int eb = g.elem_bytes;
 
@@ -333,6 +333,7 @@ __global__ __launch_bounds__(NWV * 64, 2) void gated_conv_rows_kernel(
 
   // ---- this lane's base-path pixels ------------------------------------------------------------
   int pix[NF];
+  int pimg[NF];         // image of the pixel
   bool pval[NF];
   int pa[NF][3];        // patch byte offsets of the three tap columns, kernel row 0
 #pragma unroll
@@ -343,6 +344,7 @@ __global__ __launch_bounds__(NWV * 64, 2) void gated_conv_rows_kernel(
     const int lr = fdiv3(i, g.magic_wo), wo_ = i - lr * p.wo;
     const int R = R0 + lr;
     const int img = fdiv3(R, g.magic_ho), hq = R - img * p.ho;
+    pimg[fp] = img;
     const int slot = ((img * g.hp + hq * p.stride - rho0) << g.logp) + wo_ * p.stride;
     if (lh == 0) pslot[pix[fp]] = slot;
 #pragma unroll
@@ -488,6 +490,11 @@ __global__ __launch_bounds__(NWV * 64, 2) void gated_conv_rows_kernel(
         }
       }
       if (!pval[fp]) dl = 0u;
+      if (p.chan_mask) {
+        // channel-wise gate (Sec. 3.2): only the channels that keep their conditional path in this image
+        const uint32_t* mw = p.chan_mask + (long long)pimg[fp] * p.words + cbk * 2;
+        dl &= ((mw[0] >> (16 * lh)) & 0xffffu) | (((mw[1] >> (16 * lh)) & 0xffffu) << 16);
+      }
       dlane[fp] = dl;
       bmph[pix[fp] * 4 + lh] = (uint16_t)(dl & 0xffffu);
       bmph[pix[fp] * 4 + 2 + lh] = (uint16_t)(dl >> 16);
@@ -502,6 +509,7 @@ __global__ __launch_bounds__(NWV * 64, 2) void gated_conv_rows_kernel(
         *(uint2*)(p.bitmap + (m0 + i) * p.words + cbk * 2) = w2;
       }
     }
+    if (p.gate_only) return;   // first pass of the channel-wise gate: the decisions are all it produces
     int my_prefix = 0;
     unsigned long long my_bal = 0;
 #pragma unroll

@@ -74,7 +74,8 @@ __global__ __launch_bounds__(256) void naive_kernel(Params p) {
       } else {
         fired = (acc >= p.thr_f[co]) && (acc <= p.thr_hi_f[co]);
       }
-      if (fired) {
+      if (p.chan_mask) fired = fired && ((p.chan_mask[(long long)img * p.words + (co >> 5)] >> (co & 31)) & 1u);
+      if (fired && !p.gate_only) {
         for (int r = 0; r < p.kh; ++r) {
           const int hi = ho * p.stride - p.pad + r;
           if (hi < 0 || hi >= p.h) continue;
@@ -92,12 +93,14 @@ __global__ __launch_bounds__(256) void naive_kernel(Params p) {
       }
     }
 
-    const long long o = m * p.c_out + (p.shuffle ? (co - grp * p.cpg) * p.groups + grp : co);
-    const bool branch1 = p.gated ? fired : true;
-    if constexpr (__is_same(acc_t, float)) {
-      store_float(p, o, finish_float(p, acc, branch1, co, o));
-    } else {
-      store_int(p, o, finish_int(p, acc, branch1, co, o));
+    if (!p.gate_only) {
+      const long long o = m * p.c_out + (p.shuffle ? (co - grp * p.cpg) * p.groups + grp : co);
+      const bool branch1 = p.gated ? fired : true;
+      if constexpr (__is_same(acc_t, float)) {
+        store_float(p, o, finish_float(p, acc, branch1, co, o));
+      } else {
+        store_int(p, o, finish_int(p, acc, branch1, co, o));
+      }
     }
     if (fired && p.counts) atomicAdd(&p.counts[2 + (long long)img * p.c_out + co], 1u);
   }
@@ -114,6 +117,28 @@ __global__ __launch_bounds__(256) void naive_kernel(Params p) {
 __global__ void zero_u32_kernel(uint32_t* ptr, size_t words) {
   size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (i < words) ptr[i] = 0u;
+}
+
+__global__ void chan_mask_kernel(const uint32_t* __restrict__ counts, int n, int c_out, int words, uint32_t need,
+                                 uint32_t* __restrict__ mask) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= n * words) return;
+  const int img = i / words, w = i - img * words;
+  uint32_t bits = 0u;
+  for (int b = 0; b < 32; ++b) {
+    const int co = 32 * w + b;
+    if (co < c_out && counts[2 + (long long)img * c_out + co] >= need) bits |= 1u << b;
+  }
+  mask[i] = bits;
+}
+
+hipError_t launch_chan_mask(const uint32_t* counts, int n, int c_out, int words, uint32_t need, uint32_t* mask,
+                            hipStream_t s) {
+  const int total = n * words;
+  if (total <= 0) return hipSuccess;
+  hipLaunchKernelGGL(chan_mask_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, counts, n, c_out,
+                     words, need, mask);
+  return hipGetLastError();
 }
 
 hipError_t launch_zero_u32(uint32_t* ptr, size_t words, hipStream_t s) {

@@ -47,7 +47,7 @@ def bf16_ulp(v):
 
 def run_float(inp: W.LayerInputs, gate: W.GateParams, *, in_dtype=B.CG_BF16, out_dtype=B.CG_F32,
               epilogue=B.CG_EPI_RELU, variant=B.CG_VARIANT_AUTO, affine=None, residual=None, delta_hi=None,
-              n_run=None, name="", check_counts=True, shuffle=False):
+              n_run=None, name="", check_counts=True, shuffle=False, tau_c=0.0):
     """Runs the GPU library and the oracle; asserts parity; returns a Report.  A grouped input set
     (inp.grouped) runs the layer with channel grouping; shuffle stores y channel-shuffled."""
     s = inp.shape
@@ -64,7 +64,7 @@ def run_float(inp: W.LayerInputs, gate: W.GateParams, *, in_dtype=B.CG_BF16, out
                         stride=s.stride, pad=s.pad, epilogue=epilogue, variant=variant,
                         gate_mean=gate.mean if gate else None, gate_var=gate.var if gate else None,
                         delta=gate.delta if gate else None, delta_hi=delta_hi, gate_eps=gate.eps if gate else 0.0,
-                        groups=groups, shuffle=shuffle, **aff)
+                        groups=groups, shuffle=shuffle, tau_c=tau_c, **aff)
     n = s.n if n_run is None else n_run
     res_dev = None
     res_host = None
@@ -89,22 +89,37 @@ def run_float(inp: W.LayerInputs, gate: W.GateParams, *, in_dtype=B.CG_BF16, out
         gate_eps=float(np.float32(gate.eps)) if gate else 0.0,
         scale0=f32(aff.get("scale0")), shift0=f32(aff.get("shift0")),
         scale1=f32(aff.get("scale1")), shift1=f32(aff.get("shift1")),
-        residual=res_host, epilogue=epilogue, want_partials=False, groups=groups, shuffle=shuffle)
+        residual=res_host, epilogue=epilogue, want_partials=False, groups=groups, shuffle=shuffle,
+        tau_c=float(np.float32(tau_c)))
+    need = None
+    if tau_c > 0 and gate is not None:
+        need = float(np.ceil(float(np.float32(tau_c)) * (s.ho * s.wo)))
     return compare_float(name or s.name, y, bitmap, counts, ref, s.c_out, out_dtype, variant_used, check_counts,
-                         stored_groups=groups if shuffle else 0)
+                         stored_groups=groups if shuffle else 0, chan_need=need)
 
 
 def compare_float(name, y, bitmap, counts, ref, c_out, out_dtype, variant_used, check_counts=True,
-                  stored_groups=0):
+                  stored_groups=0, chan_need=None):
     """stored_groups = G > 0: y holds the channels shuffled (channel j of group i at j*G + i) while
-    the decisions keep the natural order."""
+    the decisions keep the natural order.  chan_need = the fired count an (image, channel) needs to
+    keep its conditional path under the channel-wise gate: where the oracle's count is within the
+    number of that channel's marginal activations of it, the whole channel may go either way."""
     d_gpu = W.unpack_bitmap(bitmap, c_out).reshape(ref["d"].shape)
     d_ref = ref["d"]
     flip = d_gpu != d_ref
     nflip = int(flip.sum())
     if nflip:
-        worst = float(ref["margin"][flip].max())
-        assert worst < MARGIN, "%s: %d decision flips, worst margin %.3g >= %g" % (name, nflip, worst, MARGIN)
+        marginal = ref["margin"] < MARGIN
+        allowed = marginal
+        if chan_need is not None:
+            n_img = d_ref.shape[0]
+            pre = ref["pre_counts"].reshape(n_img, c_out).astype(np.int64)
+            slack = marginal.reshape(n_img, -1, c_out).sum(axis=1)
+            borderline = np.abs(pre - chan_need) <= slack
+            allowed = marginal | borderline[:, None, None, :]
+        bad_flip = flip & ~allowed
+        assert not bad_flip.any(), "%s: %d decision flips outside the margin %g (worst margin %.3g)" % (
+            name, int(bad_flip.sum()), MARGIN, float(ref["margin"][bad_flip].max()))
     # unused bitmap bits must be zero
     if c_out % 32:
         assert (bitmap[:, -1] >> np.uint32(c_out % 32) == 0).all(), "%s: unused bitmap bits set" % name
@@ -129,7 +144,7 @@ def compare_float(name, y, bitmap, counts, ref, c_out, out_dtype, variant_used, 
 
 
 def run_int8(q: W.Int8Inputs, thr, *, out_i8=False, epilogue=B.CG_EPI_RELU, variant=B.CG_VARIANT_AUTO,
-             rq=None, residual=None, rq_res_mult=0, n_run=None, name="", shuffle=False):
+             rq=None, residual=None, rq_res_mult=0, n_run=None, name="", shuffle=False, tau_c=0.0):
     s = q.shape
     groups = s.groups if q.grouped else 1
     x = _dev(q.x, torch.int8)
@@ -140,7 +155,7 @@ def run_int8(q: W.Int8Inputs, thr, *, out_i8=False, epilogue=B.CG_EPI_RELU, vari
     layer = B.GatedConv(n_max=s.n, h=s.h, w=s.w, c_in=s.c_in, c_out=s.c_out, c_base=q.w_base.shape[-1],
                         w_base=wb, w_cond=wc, in_dtype=B.CG_I8, out_dtype=B.CG_I8 if out_i8 else B.CG_I32,
                         kh=k, kw=k, stride=s.stride, pad=s.pad, epilogue=epilogue, variant=variant,
-                        gate_thr_i32=thr, rq_res_mult=rq_res_mult, groups=groups, shuffle=shuffle, **rq)
+                        gate_thr_i32=thr, rq_res_mult=rq_res_mult, groups=groups, shuffle=shuffle, tau_c=tau_c, **rq)
     n = s.n if n_run is None else n_run
     res_dev = _dev(residual[:n], torch.int8) if residual is not None else None
     y, bitmap, counts = layer.forward(x[:n], residual=res_dev)
@@ -153,7 +168,7 @@ def run_int8(q: W.Int8Inputs, thr, *, out_i8=False, epilogue=B.CG_EPI_RELU, vari
     ref = O.forward_int8(q.x[:n], q.w_base, q.w_cond if wc is not None else None, thr, stride=s.stride, pad=s.pad,
                          out_i8=out_i8, residual=residual[:n] if residual is not None else None,
                          rq_res_mult=rq_res_mult, epilogue=epilogue, want_partials=False, groups=groups,
-                         shuffle=shuffle, **rq)
+                         shuffle=shuffle, tau_c=float(np.float32(tau_c)), **rq)
     nm = name or s.name
     assert np.array_equal(bitmap, ref["bitmap"]), "%s: bitmap differs in %d words" % (
         nm, int((bitmap != ref["bitmap"]).sum()))

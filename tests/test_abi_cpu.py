@@ -81,6 +81,10 @@ def test_valid_descriptor_sizes_packed_buffer():
     (dict(groups=4, shuffle=2), B.CG_EINVAL),
     (dict(groups=4, variant=B.CG_VARIANT_MFMA), B.CG_EUNSUPPORTED),
     (dict(groups=4, variant=B.CG_VARIANT_MFMA_COMPACT), B.CG_EUNSUPPORTED),
+    (dict(tau_c=-0.1), B.CG_EINVAL),
+    (dict(tau_c=float("nan")), B.CG_EINVAL),
+    (dict(tau_c=float("inf")), B.CG_EINVAL),
+    (dict(tau_c=0.5, variant=B.CG_VARIANT_MFMA), B.CG_EUNSUPPORTED),
 ])
 def test_invalid_descriptors_are_rejected_without_a_gpu(over, code):
     d = make_desc(**over)
@@ -96,6 +100,7 @@ def test_grouped_descriptor_is_accepted():
     assert B.cg_conv_packed_bytes(make_desc(groups=4)) > 0
     assert B.cg_conv_packed_bytes(make_desc(groups=4, shuffle=1)) > 0
     assert B.cg_conv_packed_bytes(make_desc(groups=1)) == B.cg_conv_packed_bytes(make_desc())
+    assert B.cg_conv_packed_bytes(make_desc(tau_c=0.25)) == B.cg_conv_packed_bytes(make_desc())
 
 
 def test_missing_gate_statistics_and_nan():
