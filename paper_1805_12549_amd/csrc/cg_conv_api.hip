@@ -465,17 +465,16 @@ int cg_conv_forward(cg_conv* h, int32_t n, const void* x, const void* residual, 
     q.y = nullptr;
     q.counts = nullptr;
     q.bitmap = nullptr;
-    e = cg::launch_zero_u32(pre_counts, 2 + (size_t)n * d.c_out, s);
-    if (e == hipSuccess && h->variant == CG_VARIANT_MFMA_ROWS) {
+    if (h->variant == CG_VARIANT_MFMA_ROWS) {
       q.bitmap = (uint32_t*)(ws + wl.bitmap_off);
       e = cg::launch_mfma3(h->plan3, q, pk + l.wpk_base_off, pk + l.wpk_cond_off, s);
+      if (e == hipSuccess) e = cg::launch_bitmap_chan_mask(q, q.bitmap, need_u, mask, s);
+    } else {
+      e = cg::launch_zero_u32(pre_counts, 2 + (size_t)n * d.c_out, s);
       q.counts = pre_counts;
-      if (e == hipSuccess) e = cg::launch_bitmap_counts(q, q.bitmap, s);
-    } else if (e == hipSuccess) {
-      q.counts = pre_counts;
-      e = cg::launch_naive(q, s);
+      if (e == hipSuccess) e = cg::launch_naive(q, s);
+      if (e == hipSuccess) e = cg::launch_chan_mask(pre_counts, n, d.c_out, p.words, need_u, mask, s);
     }
-    if (e == hipSuccess) e = cg::launch_chan_mask(pre_counts, n, d.c_out, p.words, need_u, mask, s);
     p.chan_mask = mask;
   }
   if (e == hipSuccess && counts) e = cg::launch_zero_u32(counts, 2 + (size_t)n * d.c_out, s);

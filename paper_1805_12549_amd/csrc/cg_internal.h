@@ -151,6 +151,9 @@ hipError_t launch_mfma3(const Mfma3Plan& plan, const Params& p, const void* wpk_
                         hipStream_t s);
 // per-(image, channel) fired counts and their total (into p.counts, total pre-zeroed) from a decision bitmap
 hipError_t launch_bitmap_counts(const Params& p, const uint32_t* bitmap, hipStream_t s);
+// channel-wise gate: mask[img][w] bit b = (fired count of channel 32*w + b in image img, from the bitmap) >= need
+hipError_t launch_bitmap_chan_mask(const Params& p, const uint32_t* bitmap, uint32_t need, uint32_t* mask,
+                                   hipStream_t s);
 
 // channel-wise gate: mask[img][w] bit b = counts[2 + img*c_out + 32*w + b] >= need
 hipError_t launch_chan_mask(const uint32_t* counts, int n, int c_out, int words, uint32_t need, uint32_t* mask,

@@ -778,36 +778,42 @@ __global__ void pack_rows_kernel(const char* __restrict__ w, char* __restrict__ 
   *(i32x4*)(out + id * 16) = v;
 }
 
-// per-(image, channel) fired counts and their total from the decision bitmap
+// per-(image, channel) fired counts and their total from the decision bitmap: one block per
+// (image, bitmap word); a wavefront takes 64 pixels at a time and counts bit b of their words with
+// a ballot, lane b keeping the running count; one atomic per block adds to the total.  With `mask`
+// the block instead writes the word of the channels whose count reaches `need` (the channel-wise
+// gate of Sec. 3.2) and leaves `counts` alone.
 __global__ void bitmap_counts_kernel(const uint32_t* __restrict__ bitmap, int words, int hw, int c_out,
-                                     uint32_t* __restrict__ counts) {
+                                     uint32_t* __restrict__ counts, uint32_t* __restrict__ mask, uint32_t need) {
   __shared__ uint32_t cnt[32];
   const int w = blockIdx.x % words, img = blockIdx.x / words;
+  const int lane = threadIdx.x & 63;
   if (threadIdx.x < 32) cnt[threadIdx.x] = 0u;
   __syncthreads();
-  uint32_t mine[32];
+  uint32_t mine = 0u;
+  for (int base = (int)(threadIdx.x & ~63u); base < hw; base += (int)blockDim.x) {
+    const int px = base + lane;
+    const uint32_t v = px < hw ? bitmap[((long long)img * hw + px) * words + w] : 0u;
 #pragma unroll
-  for (int b = 0; b < 32; ++b) mine[b] = 0u;
-  for (int px = threadIdx.x; px < hw; px += blockDim.x) {
-    const uint32_t v = bitmap[((long long)img * hw + px) * words + w];
-#pragma unroll
-    for (int b = 0; b < 32; ++b) mine[b] += (v >> b) & 1u;
-  }
-#pragma unroll
-  for (int b = 0; b < 32; ++b) {
-    uint32_t v = mine[b];
-#pragma unroll
-    for (int sft = 32; sft >= 1; sft >>= 1) v += (uint32_t)__shfl_xor((int)v, sft, 64);
-    if ((threadIdx.x & 63) == 0 && v) atomicAdd(&cnt[b], v);
-  }
-  __syncthreads();
-  if (threadIdx.x < 32) {
-    const int co = w * 32 + threadIdx.x;
-    const uint32_t v = cnt[threadIdx.x];
-    if (co < c_out) {
-      counts[2 + (long long)img * c_out + co] = v;
-      if (v) atomicAdd((unsigned long long*)counts, (unsigned long long)v);
+    for (int b = 0; b < 32; ++b) {
+      const uint32_t nb = (uint32_t)__popcll(__ballot((v >> b) & 1u));
+      mine += lane == b ? nb : 0u;
     }
+  }
+  if (lane < 32 && mine) atomicAdd(&cnt[lane], mine);
+  __syncthreads();
+  if (threadIdx.x < 64) {
+    const int co = w * 32 + lane;
+    uint32_t v = (lane < 32 && co < c_out) ? cnt[lane] : 0u;
+    if (mask) {
+      const unsigned long long keep = __ballot(lane < 32 && co < c_out && v >= need);
+      if (lane == 0) mask[(long long)img * words + w] = (uint32_t)keep;
+      return;
+    }
+    if (lane < 32 && co < c_out) counts[2 + (long long)img * c_out + co] = v;
+#pragma unroll
+    for (int sft = 16; sft >= 1; sft >>= 1) v += (uint32_t)__shfl_xor((int)v, sft, 64);
+    if (lane == 0 && v) atomicAdd((unsigned long long*)counts, (unsigned long long)v);
   }
 }
 
@@ -977,7 +983,16 @@ hipError_t launch_bitmap_counts(const Params& p, const uint32_t* bitmap, hipStre
   const long long blocks = (long long)p.n * p.words;
   if (blocks <= 0) return hipSuccess;
   hipLaunchKernelGGL(bitmap_counts_kernel, dim3((unsigned)blocks), dim3(256), 0, s, bitmap, p.words, p.ho * p.wo,
-                     p.c_out, p.counts);
+                     p.c_out, p.counts, (uint32_t*)nullptr, 0u);
+  return hipGetLastError();
+}
+
+hipError_t launch_bitmap_chan_mask(const Params& p, const uint32_t* bitmap, uint32_t need, uint32_t* mask,
+                                   hipStream_t s) {
+  const long long blocks = (long long)p.n * p.words;
+  if (blocks <= 0) return hipSuccess;
+  hipLaunchKernelGGL(bitmap_counts_kernel, dim3((unsigned)blocks), dim3(256), 0, s, bitmap, p.words, p.ho * p.wo,
+                     p.c_out, (uint32_t*)nullptr, mask, need);
   return hipGetLastError();
 }
 
