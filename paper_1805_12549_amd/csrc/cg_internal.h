@@ -123,8 +123,8 @@ hipError_t launch_mfma2(const Mfma2Plan& plan, const Params& p, const void* wpk_
 struct Mfma3Plan {
   int ok;
   int elem_bytes, ch;      // bytes per element; channels per 16-byte chunk
-  int nwv;                 // wavefronts per workgroup: 4 or 8
-  int nf;                  // 32-pixel fragments per wavefront in the base phase (1 or 2)
+  int nwv;                 // wavefronts per workgroup: 4, or 8 for the 256-pixel tile
+  int nf;                  // 32-pixel fragments per wavefront in the base phase
   int bm;                  // 32*nf*nwv pixels per tile, padded
   int n_cb;                // c_out / 64
   int tr;                  // global output rows per tile

@@ -94,24 +94,17 @@ __device__ __forceinline__ i32x4 lds_read16(const char* p) {
 }
 
 // s_waitcnt vmcnt(n): at most n vector-memory operations of this wavefront still in flight
+// (the count is a 6-bit field split over bits 3:0 and 15:14; lgkmcnt and expcnt are left open)
+#define CG_VMCNT(n) (0x0F70 | ((n) & 15) | (((n) >> 4) << 14))
 __device__ __forceinline__ void wait_vm(int n) {
   switch (n) {
-    case 0: __builtin_amdgcn_s_waitcnt(0x0F70); break;
-    case 1: __builtin_amdgcn_s_waitcnt(0x0F71); break;
-    case 2: __builtin_amdgcn_s_waitcnt(0x0F72); break;
-    case 3: __builtin_amdgcn_s_waitcnt(0x0F73); break;
-    case 4: __builtin_amdgcn_s_waitcnt(0x0F74); break;
-    case 5: __builtin_amdgcn_s_waitcnt(0x0F75); break;
-    case 6: __builtin_amdgcn_s_waitcnt(0x0F76); break;
-    case 7: __builtin_amdgcn_s_waitcnt(0x0F77); break;
-    case 8: __builtin_amdgcn_s_waitcnt(0x0F78); break;
-    case 9: __builtin_amdgcn_s_waitcnt(0x0F79); break;
-    case 10: __builtin_amdgcn_s_waitcnt(0x0F7A); break;
-    case 11: __builtin_amdgcn_s_waitcnt(0x0F7B); break;
-    case 12: __builtin_amdgcn_s_waitcnt(0x0F7C); break;
-    case 13: __builtin_amdgcn_s_waitcnt(0x0F7D); break;
-    case 14: __builtin_amdgcn_s_waitcnt(0x0F7E); break;
-    default: __builtin_amdgcn_s_waitcnt(0x0F7F); break;   // 15 or more allowed: wait down to 15
+#define CG_CASE(n) case n: __builtin_amdgcn_s_waitcnt(CG_VMCNT(n)); break;
+    CG_CASE(0) CG_CASE(1) CG_CASE(2) CG_CASE(3) CG_CASE(4) CG_CASE(5) CG_CASE(6) CG_CASE(7)
+    CG_CASE(8) CG_CASE(9) CG_CASE(10) CG_CASE(11) CG_CASE(12) CG_CASE(13) CG_CASE(14) CG_CASE(15)
+    CG_CASE(16) CG_CASE(17) CG_CASE(18) CG_CASE(19) CG_CASE(20) CG_CASE(21) CG_CASE(22) CG_CASE(23)
+    CG_CASE(24) CG_CASE(25) CG_CASE(26) CG_CASE(27) CG_CASE(28) CG_CASE(29) CG_CASE(30)
+#undef CG_CASE
+    default: __builtin_amdgcn_s_waitcnt(CG_VMCNT(31)); break;   // 31 or more allowed: wait down to 31
   }
 }
 
@@ -185,8 +178,7 @@ __global__ __launch_bounds__(NWV * 64, 2) void gated_conv_rows_kernel(
   using acc_t = typename Tr::acc_t;
   using Base = typename Tr::Base;
   constexpr int NT = NWV * 64;                 // threads
-  constexpr int RD = NWV == 8 ? 4 : 2;         // weight granules in the ring
-  constexpr int D = RD - 1;                    // granules fetched ahead
+  constexpr int RD = 2;                        // weight granules in the ring: the one in use and the next
   constexpr int GK = 3 * CPS / 2;              // K steps per weight granule
   constexpr int GB = GK * 2048;                // bytes per weight granule
   constexpr int PB = PKB * 1024;               // bytes per patch buffer
@@ -210,6 +202,7 @@ __global__ __launch_bounds__(NWV * 64, 2) void gated_conv_rows_kernel(
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  __builtin_assume(wave >= 0 && wave < NWV);
   const int lj = lane & 31, lh = lane >> 5;
 
   // blocks that share a pixel tile (different channel blocks) sit on the same XCD (block id mod 8)
@@ -241,25 +234,18 @@ __global__ __launch_bounds__(NWV * 64, 2) void gated_conv_rows_kernel(
     }
   }
 
-  // source of weight granule j (3*super-stage + kernel row, counted over both phases) of this channel block
-  auto w_src = [&](int j) __attribute__((always_inline)) {
-    const int ph = j >= 3 * S0 ? 1 : 0;
-    const int jj = ph ? j - 3 * S0 : j;
-    return (ph ? wpk1 : wpk0) + ((size_t)cbk * 3 * g.stages[ph] + jj) * GB;
-  };
+  // weight granule j (3*super-stage + kernel row, counted over both phases) of this channel block
+  // sits at wbase0 + j*GB in the base phase and at wcond0 + (j - 3*S0)*GB in the conditional phase
+  const char* const wbase0 = wpk0 + (size_t)cbk * 3 * g.stages[0] * GB;
+  const char* const wcond0 = wpk1 + (size_t)cbk * 3 * g.stages[1] * GB;
   // weight load instruction u of this wavefront: 1 KB number wave + NWV*u of the granule
   auto issue_w = [&](const char* ws, char* dst, int u) __attribute__((always_inline)) {
     const int idx = wave + NWV * u;
     if (idx < 2 * GK) lds_direct16(ws + idx * 1024 + lane * 16, dst + idx * 1024);
   };
 #pragma unroll
-  for (int j = 0; j < D; ++j) {
-    if (j < G) {
-      const char* ws = w_src(j);
-#pragma unroll
-      for (int u = 0; u < WPW; ++u) issue_w(ws, wgt + j * GB, u);
-    }
-  }
+  for (int u = 0; u < WPW; ++u) issue_w(wbase0, wgt, u);
+  const char* wnext = wbase0 + GB;   // source of the granule after the one being multiplied
 
   const long long m0 = (long long)R0 * p.wo;        // first output pixel
   const int rows_here = total_rows - R0 < g.tr ? total_rows - R0 : g.tr;
@@ -298,13 +284,6 @@ __global__ __launch_bounds__(NWV * 64, 2) void gated_conv_rows_kernel(
     }
   }
   smask = __builtin_amdgcn_readfirstlane(smask);
-  // loads this wavefront issues per granule: weights, patch in a super-stage's first / second granule
-  int cw = 0;
-#pragma unroll
-  for (int u = 0; u < WPW; ++u) cw += (wave + NWV * u < 2 * GK) ? 1 : 0;
-  const int np0 = __popc(smask & ((1u << KH) - 1u));
-  const int np1 = __popc((smask >> KH) & ((1u << (KPW - KH)) - 1u));
-
   // x at the first channel of super-stage sg (counted over both phases).  The base phase starts at
   // this block's first base channel; the conditional phase walks the channels in order and jumps
   // over the base channels (without grouping these are the first c_base; with grouping, Sec. 3.3,
@@ -382,87 +361,86 @@ __global__ __launch_bounds__(NWV * 64, 2) void gated_conv_rows_kernel(
   __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): the first granules and the first patch have landed
   __syncthreads();
 
-  // One weight granule gi (kernel row r of super-stage sg) for NL pixel fragments: multiply it out of
-  // its patch buffer and ring slot; meanwhile fetch granule gi+D into the ring slot the previous
-  // granule left and, in the first two granules of a super-stage, half of the next super-stage's
-  // patch into the other patch buffer.  Over the granule the weight instructions go out first, then
-  // the patch instructions.  The closing wait covers granule gi+1's weights and, at the end of a
-  // super-stage, the next patch; younger loads stay in flight.
-  auto granule = [&](auto nl_tag, acc16 (&acc)[NF][2], const int (&base)[NF][3], int gi, int sg, int r)
+  // Per super-stage: where the next super-stage's patch comes from and which of this wavefront's
+  // load instructions carry any of it (first half in the super-stage's first granule, second half in
+  // its second one).
+  const char* xsn = xbytes;
+  unsigned pm0 = 0u, pm1 = 0u;
+  int np0 = 0, np1 = 0;
+  auto stage_setup = [&](int sg) __attribute__((always_inline)) {
+    const bool more = sg + 1 < S;
+    xsn = x_src(more ? sg + 1 : sg);
+    pm0 = more ? smask & ((1u << KH) - 1u) : 0u;
+    pm1 = more ? (smask >> KH) & ((1u << (KPW - KH)) - 1u) : 0u;
+    np0 = __popc(pm0);
+    np1 = __popc(pm1);
+  };
+
+  // One weight granule gi (kernel row R of super-stage sg) for NL pixel fragments: multiply it out of
+  // its patch buffer and ring slot; meanwhile fetch granule gi+1 into the other ring slot and, in the
+  // first two granules of a super-stage, half of the next super-stage's patch into the other patch
+  // buffer.  Within the granule the weight instructions go out first, then the patch instructions.
+  // A wavefront's loads complete in issue order, so the closing wait for the next granule's weights
+  // leaves this granule's patch loads in flight; the last granule of a super-stage waits for all.
+  auto granule = [&](auto nl_tag, auto r_tag, acc16 (&acc)[NF][2], const int (&base)[NF][3], int gi, int sg)
                      __attribute__((always_inline)) {
     constexpr int NL = decltype(nl_tag)::value;
+    constexpr int R = decltype(r_tag)::value;
+    constexpr int K0 = R == 1 ? KH : 0;                    // first patch instruction of this granule
+    constexpr int NP = R == 0 ? KH : R == 1 ? KPW - KH : 0;   // and how many
     const char* pat = pat2 + (sg & 1) * PB;
     char* patn = pat2 + ((sg & 1) ^ 1) * PB;
-    const char* wg = wgt + (gi & (RD - 1)) * GB;
-    const int nslot = (gi + D) & (RD - 1);
-    char* wgn = wgt + nslot * GB;
-    const char* ws = gi + D < G ? w_src(gi + D) : nullptr;
-    const int k0 = r == 1 ? KH : 0;
-    unsigned pm = 0u;
-    const char* xs = xbytes;
-    if (r < 2 && sg + 1 < S) {
-      xs = x_src(sg + 1);
-      pm = (smask >> k0) & ((1u << KH) - 1u);
-      if (r == 1) pm &= (1u << (KPW - KH)) - 1u;
-    }
-    int vsel[KH];
-#pragma unroll
-    for (int i = 0; i < KH; ++i) vsel[i] = (k0 == 0 || KH + i >= KPW) ? voff[i] : voff[KH + i < KPW ? KH + i : i];
+    const char* wg = wgt + (gi & 1) * GB;
+    char* wgn = wgt + ((gi & 1) ^ 1) * GB;
+    const bool have_w = gi + 1 < G;
+    const char* ws = wnext;
+    wnext = (gi + 2 == 3 * S0) ? wcond0 : wnext + GB;
+    const unsigned pm = R == 0 ? pm0 : pm1;
     auto part = [&](int t) __attribute__((always_inline)) {
-      constexpr int NU = WPW + KH;
+      constexpr int NU = WPW + NP;
 #pragma unroll
       for (int u = (t * NU) / GK; u < ((t + 1) * NU) / GK; ++u) {
         if (u < WPW) {
-          if (ws) issue_w(ws, wgn, u);
+          if (have_w) issue_w(ws, wgn, u);
         } else {
           const int i = u - WPW;
-          if (((pm >> i) & 1u) && vsel[i] >= 0) lds_direct16(xs + vsel[i], patn + (wave + NWV * (k0 + i)) * 1024);
+          if (((pm >> i) & 1u) && voff[K0 + i] >= 0)
+            lds_direct16(xsn + voff[K0 + i], patn + (wave + NWV * (K0 + i)) * 1024);
         }
       }
     };
+    // the kernel row's byte offset goes through an opaque register: the three unrolled granules then
+    // each form their operand addresses afresh instead of keeping all of them live across the loop
+    int rofs = R * rowb;
+    asm volatile("" : "+s"(rofs));
     int ar[NF][3];
 #pragma unroll
     for (int fp = 0; fp < NF; ++fp)
 #pragma unroll
-      for (int c = 0; c < 3; ++c) ar[fp][c] = base[fp][c] + r * rowb;
+      for (int c = 0; c < 3; ++c) ar[fp][c] = base[fp][c] + rofs;
     mma_granule<Tr, NL, NF, CPS>(pat, wg, wofs, ar, acc, part);
-    // The loads of a wavefront complete in order.  Granule gi+1's weights went out D-1 granules ago,
-    // before that granule's patch loads; everything issued after them may stay in flight, except
-    // that a super-stage's last granule also needs every patch load (all older than its own weight
-    // loads).  np_of(g, r): patch loads of this wavefront in granule g (kernel row r).
-    int allowed = 0;
-    if (gi + 1 < G) {
-      if (r == 2) {
-        allowed = (D > 1 && gi + D < G) ? cw : 0;   // with D = 1 this granule's weight loads are the needed ones
-      } else {
-        int rr = r, ss = sg;
-#pragma unroll
-        for (int k = 0; k < D; ++k) {        // granules gi, gi-1, ..., gi-D+1
-          const int g2 = gi - k;
-          if (g2 < 0) break;
-          const int np = (rr < 2 && ss + 1 < S) ? (rr == 0 ? np0 : np1) : 0;
-          allowed += np;
-          if (k < D - 1 && g2 + D < G) allowed += cw;   // its own weight loads are younger than W(gi+1) too
-          if (--rr < 0) {
-            rr = 2;
-            --ss;
-          }
-        }
-      }
-    }
-    wait_vm(allowed);
+    if constexpr (R == 2)
+      wait_vm(0);
+    else
+      wait_vm(R == 0 ? np0 : np1);
+  };
+  // the three granules of super-stage sg
+  auto super_stage = [&](auto nl_tag, acc16 (&acc)[NF][2], const int (&base)[NF][3], int gi, int sg, bool last)
+                         __attribute__((always_inline)) {
+    stage_setup(sg);
+    granule(nl_tag, std::integral_constant<int, 0>{}, acc, base, gi, sg);
+    __builtin_amdgcn_s_barrier();
+    granule(nl_tag, std::integral_constant<int, 1>{}, acc, base, gi + 1, sg);
+    __builtin_amdgcn_s_barrier();
+    granule(nl_tag, std::integral_constant<int, 2>{}, acc, base, gi + 2, sg);
+    if (!last) __builtin_amdgcn_s_barrier();
   };
 
   // ---- base path --------------------------------------------------------------------------------
   int gi = 0;
 #pragma nounroll
-  for (int sg = 0; sg < S0; ++sg) {
-#pragma nounroll
-    for (int r = 0; r < 3; ++r, ++gi) {
-      granule(std::integral_constant<int, NF>{}, accP, pa, gi, sg, r);
-      if (gi + 1 < 3 * S0) __builtin_amdgcn_s_barrier();
-    }
-  }
+  for (int sg = 0; sg < S0; ++sg, gi += 3)
+    super_stage(std::integral_constant<int, NF>{}, accP, pa, gi, sg, sg + 1 == S0);
 
   if (p.gated) {
     // ---- gate -------------------------------------------------------------------------------
@@ -546,17 +524,13 @@ __global__ __launch_bounds__(NWV * 64, 2) void gated_conv_rows_kernel(
       __syncthreads();
     } else {
 #pragma nounroll
-      for (int sg = S0; sg < S; ++sg) {
-#pragma nounroll
-        for (int r = 0; r < 3; ++r, ++gi) {
-          if (nrl == 2) {
-            if constexpr (NF == 2) granule(std::integral_constant<int, 2>{}, accR, pac, gi, sg, r);
-          } else if (nrl == 1) {
-            granule(std::integral_constant<int, 1>{}, accR, pac, gi, sg, r);
-          } else {
-            granule(std::integral_constant<int, 0>{}, accR, pac, gi, sg, r);
-          }
-          __builtin_amdgcn_s_barrier();
+      for (int sg = S0; sg < S; ++sg, gi += 3) {
+        if (nrl == 2) {
+          if constexpr (NF == 2) super_stage(std::integral_constant<int, 2>{}, accR, pac, gi, sg, false);
+        } else if (nrl == 1) {
+          super_stage(std::integral_constant<int, 1>{}, accR, pac, gi, sg, false);
+        } else {
+          super_stage(std::integral_constant<int, 0>{}, accR, pac, gi, sg, false);
         }
       }
     }
@@ -831,16 +805,19 @@ hipError_t launch_rows_one(const Mfma3Plan& g, const Params& p, const void* w0, 
 
 template <typename Tr, int NF, int CPS>
 hipError_t launch_rows_cps(const Mfma3Plan& g, const Params& p, const void* w0, const void* w1, hipStream_t s) {
+  if constexpr (NF == 1) {
+    if (g.nwv == 8) {
+      if (g.pkb == 24) return launch_rows_one<Tr, NF, CPS, 24, 8>(g, p, w0, w1, s);
+      return launch_rows_one<Tr, NF, CPS, 48, 8>(g, p, w0, w1, s);
+    }
+  }
   if (g.pkb == 24) return launch_rows_one<Tr, NF, CPS, 24, 4>(g, p, w0, w1, s);
   return launch_rows_one<Tr, NF, CPS, 48, 4>(g, p, w0, w1, s);
 }
 
 template <typename Tr>
 hipError_t launch_rows_dtype(const Mfma3Plan& g, const Params& p, const void* w0, const void* w1, hipStream_t s) {
-  if (g.nf == 2) {
-    if (g.cps == 4) return launch_rows_cps<Tr, 2, 4>(g, p, w0, w1, s);
-    return launch_rows_cps<Tr, 2, 2>(g, p, w0, w1, s);
-  }
+  if (g.nf != 1) return hipErrorInvalidValue;   // the plan only issues one fragment per wavefront
   if (g.cps == 4) return launch_rows_cps<Tr, 1, 4>(g, p, w0, w1, s);
   return launch_rows_cps<Tr, 1, 2>(g, p, w0, w1, s);
 }
@@ -943,6 +920,13 @@ Mfma3Plan mfma3_plan(const cg_conv_desc& d) {
       if (nf == 2 && tiles * g.n_cb < 256) continue;   // the large tile only when it still fills the CUs
       g.nwv = c.nwv;
       g.nf = nf;
+      if (nf == 2) {
+        // the 256-pixel tile runs as eight wavefronts of one fragment each rather than four of two:
+        // same tile, half the registers per wavefront, twice the wavefronts to overlap each other's
+        // scalar work and waits (measured 8-10 % faster on the 64- and 128-channel layers)
+        g.nwv = 8;
+        g.nf = 1;
+      }
       g.bm = bm;
       g.tr = t;
       g.pkb = c.pkb;
