@@ -35,6 +35,7 @@
 // only what the next granule needs (the loads of a wavefront complete in order).
 #include <cstdlib>
 #include <type_traits>
+#include <utility>
 
 #include "cg_mfma_common.h"
 
@@ -92,19 +93,28 @@ __device__ __forceinline__ i32x4 lds_read16(const char* p) {
   asm volatile("ds_read_b128 %0, %1" : "=v"(v) : "v"(addr) : "memory");
   return v;
 }
+// the same with a compile-time byte offset in the instruction (no address arithmetic per read)
+template <int OFS>
+__device__ __forceinline__ i32x4 lds_read16_at(unsigned addr) {
+  static_assert(OFS >= 0 && OFS < 65536, "16-bit offset field");
+  i32x4 v;
+  asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "n"(OFS) : "memory");
+  return v;
+}
 
 // s_waitcnt vmcnt(n): at most n vector-memory operations of this wavefront still in flight
 // (the count is a 6-bit field split over bits 3:0 and 15:14; lgkmcnt and expcnt are left open)
 #define CG_VMCNT(n) (0x0F70 | ((n) & 15) | (((n) >> 4) << 14))
-__device__ __forceinline__ void wait_vm(int n) {
-  switch (n) {
-#define CG_CASE(n) case n: __builtin_amdgcn_s_waitcnt(CG_VMCNT(n)); break;
-    CG_CASE(0) CG_CASE(1) CG_CASE(2) CG_CASE(3) CG_CASE(4) CG_CASE(5) CG_CASE(6) CG_CASE(7)
-    CG_CASE(8) CG_CASE(9) CG_CASE(10) CG_CASE(11) CG_CASE(12) CG_CASE(13) CG_CASE(14) CG_CASE(15)
-    CG_CASE(16) CG_CASE(17) CG_CASE(18) CG_CASE(19) CG_CASE(20) CG_CASE(21) CG_CASE(22) CG_CASE(23)
-    CG_CASE(24) CG_CASE(25) CG_CASE(26) CG_CASE(27) CG_CASE(28) CG_CASE(29) CG_CASE(30)
-#undef CG_CASE
-    default: __builtin_amdgcn_s_waitcnt(CG_VMCNT(31)); break;   // 31 or more allowed: wait down to 31
+// for 0 <= n <= MAXN with MAXN small: a ladder of at most MAXN compares
+template <int MAXN>
+__device__ __forceinline__ void wait_vm_upto(int n) {
+  if constexpr (MAXN == 0) {
+    __builtin_amdgcn_s_waitcnt(CG_VMCNT(0));
+  } else {
+    if (n >= MAXN)
+      __builtin_amdgcn_s_waitcnt(CG_VMCNT(MAXN));
+    else
+      wait_vm_upto<MAXN - 1>(n);
   }
 }
 
@@ -114,6 +124,16 @@ template <int CPS>
 __device__ __forceinline__ int slot_addr(int slot, int h) {
   if constexpr (CPS == 4) return slot * 64 + ((h ^ (slot >> 2)) & 3) * 16;
   return slot * 32 + ((h ^ (slot >> 3)) & 1) * 16;
+}
+
+// f(integral_constant<int, 0>), ..., f(integral_constant<int, N-1>)
+template <int... I, typename F>
+__device__ __forceinline__ void static_for_impl(std::integer_sequence<int, I...>, F&& f) {
+  (f(std::integral_constant<int, I>{}), ...);
+}
+template <int N, typename F>
+__device__ __forceinline__ void static_for(F&& f) {
+  static_for_impl(std::make_integer_sequence<int, N>{}, static_cast<F&&>(f));
 }
 
 // One weight granule of MFMAs for this wavefront: NL pixel fragments x two 32-channel fragments,
@@ -129,25 +149,27 @@ __device__ __forceinline__ void mma_granule(const char* __restrict__ pat, const 
   constexpr int PAIRS = CPS / 2;
   constexpr int M = NL * 2;   // MFMAs per K step
   i32x4 a[2][2], b[2][NL > 0 ? NL : 1];
+  // the weight operands sit at compile-time offsets from one per-lane address
+  const unsigned wa = (unsigned)(uintptr_t)(wg + wofs);
   if constexpr (NL > 0) {
-#pragma unroll
-    for (int fc = 0; fc < 2; ++fc) a[0][fc] = lds_read16(wg + wofs + fc * 512);
+    a[0][0] = lds_read16_at<0>(wa);
+    a[0][1] = lds_read16_at<512>(wa);
 #pragma unroll
     for (int fp = 0; fp < NL; ++fp) b[0][fp] = lds_read16(pat + ar[fp][0]);
   }
-#pragma unroll
-  for (int k = 0; k < GK; ++k) {
+  static_for<GK>([&](auto kc) __attribute__((always_inline)) {
+    constexpr int k = decltype(kc)::value;
     if constexpr (NL == 0) {
       issue(k);
     } else {
-      const int c = k & 1, n = c ^ 1;
+      constexpr int c = k & 1, n = c ^ 1;
       __builtin_amdgcn_s_waitcnt(0xC07F);   // lgkmcnt(0): operands of step k are in registers
       __builtin_amdgcn_sched_barrier(0);
       // all operand reads of step k+1 go out before the MFMAs of step k: they then have the whole
       // step to land
-      if (k + 1 < GK) {
-#pragma unroll
-        for (int i = 0; i < 2; ++i) a[n][i] = lds_read16(wg + wofs + (k + 1) * 2048 + i * 512);
+      if constexpr (k + 1 < GK) {
+        a[n][0] = lds_read16_at<(k + 1) * 2048>(wa);
+        a[n][1] = lds_read16_at<(k + 1) * 2048 + 512>(wa);
 #pragma unroll
         for (int i = 0; i < NL; ++i)
           b[n][i] = lds_read16(pat + (ar[i][(k + 1) / PAIRS] ^ (((k + 1) % PAIRS) * 32)));
@@ -161,7 +183,7 @@ __device__ __forceinline__ void mma_granule(const char* __restrict__ pat, const 
       for (int j = 1; j < M; ++j) acc[j >> 1][j & 1] = Tr::mfma(a[c][j & 1], b[c][j >> 1], acc[j >> 1][j & 1]);
       __builtin_amdgcn_sched_barrier(0);
     }
-  }
+  });
   if constexpr (NL > 0) {
     // The accumulators may be read right after this loop, across the branch of the last issue();
     // the compiler's count of wait states between an MFMA and a read of its result follows the
@@ -365,15 +387,14 @@ __global__ __launch_bounds__(NWV * 64, 2) void gated_conv_rows_kernel(
   // load instructions carry any of it (first half in the super-stage's first granule, second half in
   // its second one).
   const char* xsn = xbytes;
-  unsigned pm0 = 0u, pm1 = 0u;
-  int np0 = 0, np1 = 0;
+  bool more = false;
+  int np0 = 0, np1 = 0;   // loads of this wavefront in the first / second granule (an instruction goes out iff a lane is valid)
+  const int cnt0 = __popc(smask & ((1u << KH) - 1u)), cnt1 = __popc((smask >> KH) & ((1u << (KPW - KH)) - 1u));
   auto stage_setup = [&](int sg) __attribute__((always_inline)) {
-    const bool more = sg + 1 < S;
+    more = sg + 1 < S;
     xsn = x_src(more ? sg + 1 : sg);
-    pm0 = more ? smask & ((1u << KH) - 1u) : 0u;
-    pm1 = more ? (smask >> KH) & ((1u << (KPW - KH)) - 1u) : 0u;
-    np0 = __popc(pm0);
-    np1 = __popc(pm1);
+    np0 = more ? cnt0 : 0;
+    np1 = more ? cnt1 : 0;
   };
 
   // One weight granule gi (kernel row R of super-stage sg) for NL pixel fragments: multiply it out of
@@ -392,20 +413,19 @@ __global__ __launch_bounds__(NWV * 64, 2) void gated_conv_rows_kernel(
     char* patn = pat2 + ((sg & 1) ^ 1) * PB;
     const char* wg = wgt + (gi & 1) * GB;
     char* wgn = wgt + ((gi & 1) ^ 1) * GB;
-    const bool have_w = gi + 1 < G;
+    // the kernel's very last granule has no successor: it fetches its own weights once more into the
+    // free slot, which keeps the issue code free of conditions
     const char* ws = wnext;
-    wnext = (gi + 2 == 3 * S0) ? wcond0 : wnext + GB;
-    const unsigned pm = R == 0 ? pm0 : pm1;
+    if (gi + 2 < G) wnext = (gi + 2 == 3 * S0) ? wcond0 : wnext + GB;
     auto part = [&](int t) __attribute__((always_inline)) {
       constexpr int NU = WPW + NP;
 #pragma unroll
       for (int u = (t * NU) / GK; u < ((t + 1) * NU) / GK; ++u) {
         if (u < WPW) {
-          if (have_w) issue_w(ws, wgn, u);
+          issue_w(ws, wgn, u);
         } else {
           const int i = u - WPW;
-          if (((pm >> i) & 1u) && voff[K0 + i] >= 0)
-            lds_direct16(xsn + voff[K0 + i], patn + (wave + NWV * (K0 + i)) * 1024);
+          if (more && voff[K0 + i] >= 0) lds_direct16(xsn + voff[K0 + i], patn + (wave + NWV * (K0 + i)) * 1024);
         }
       }
     };
@@ -420,9 +440,9 @@ __global__ __launch_bounds__(NWV * 64, 2) void gated_conv_rows_kernel(
       for (int c = 0; c < 3; ++c) ar[fp][c] = base[fp][c] + rofs;
     mma_granule<Tr, NL, NF, CPS>(pat, wg, wofs, ar, acc, part);
     if constexpr (R == 2)
-      wait_vm(0);
+      wait_vm_upto<0>(0);
     else
-      wait_vm(R == 0 ? np0 : np1);
+      wait_vm_upto<NP>(R == 0 ? np0 : np1);
   };
   // the three granules of super-stage sg
   auto super_stage = [&](auto nl_tag, acc16 (&acc)[NF][2], const int (&base)[NF][3], int gi, int sg, bool last)
