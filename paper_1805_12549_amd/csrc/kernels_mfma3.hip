@@ -558,13 +558,16 @@ __global__ __launch_bounds__(NWV * 64, 2) void gated_conv_rows_kernel(
     __syncthreads();
   }
 
-  // ---- combine: R (compacted rows) goes through LDS, 64 rows at a time, to the lanes that hold P ----
+  // ---- combine: R (compacted rows) goes through LDS, 128 rows at a time, to the lanes that hold P ----
   if (p.gated && n_act > 0) {
-    const int npass = (n_act + 63) >> 6;
+    constexpr int FPP = 4;                 // compacted fragments per pass
+    static_assert(FPP <= NWV && FPP * 32 * kRs <= 2 * PB, "a pass must fit the patch buffers");
+    const int npass = (n_act + 32 * FPP - 1) / (32 * FPP);
     for (int q = 0; q < npass; ++q) {
-      // compacted fragments 2q and 2q+1 belong to wavefronts (2q)%NWV and the next, their slot (2q)/NWV
-      const int w0 = (2 * q) & (NWV - 1), kk = (2 * q) / NWV;
-      if ((wave == w0 || wave == w0 + 1) && nrl > kk) {
+      // compacted fragments FPP*q .. FPP*q+FPP-1 belong to wavefronts (FPP*q)%NWV and the following
+      // ones, all in their slot (FPP*q)/NWV
+      const int w0 = (FPP * q) & (NWV - 1), kk = (FPP * q) / NWV;
+      if (wave >= w0 && wave < w0 + FPP && nrl > kk) {
         char* row = pat2 + ((wave - w0) * 32 + lj) * kRs + lh * 64;
 #pragma unroll
         for (int k = 0; k < NF; ++k) {
@@ -587,8 +590,8 @@ __global__ __launch_bounds__(NWV * 64, 2) void gated_conv_rows_kernel(
 #pragma unroll
       for (int fp = 0; fp < NF; ++fp) {
         if (dlane[fp]) {
-          const int r = (int)rank[pix[fp]] - 64 * q;
-          if (r >= 0 && r < 64) {
+          const int r = (int)rank[pix[fp]] - 32 * FPP * q;
+          if (r >= 0 && r < 32 * FPP) {
             const char* row = pat2 + r * kRs + lh * 64;
 #pragma unroll
             for (int fc = 0; fc < 2; ++fc)
