@@ -125,7 +125,8 @@ struct Mfma3Plan {
   int elem_bytes, ch;      // bytes per element; channels per 16-byte chunk
   int nwv;                 // wavefronts per workgroup: 4, or 8 for the 256-pixel tile
   int nf;                  // 32-pixel fragments per wavefront in the base phase
-  int bm;                  // 32*nf*nwv pixels per tile, padded
+  int nc;                  // 32-channel fragments per wavefront: 2, or 1 when two wavefronts share a pixel fragment
+  int bm;                  // 32*nf*nwv*nc/2 pixels per tile, padded
   int n_cb;                // c_out / 64
   int tr;                  // global output rows per tile
   int hp;                  // h + 2*pad
