@@ -126,6 +126,7 @@ struct Mfma3Plan {
   int nwv;                 // wavefronts per workgroup: 4, or 8 for the 256-pixel tile
   int nf;                  // 32-pixel fragments per wavefront in the base phase
   int nc;                  // 32-channel fragments per wavefront: 2, or 1 when two wavefronts share a pixel fragment
+  int ldw;                 // wavefronts (of nwv) that only issue the LDS-direct loads: 0 or 4
   int bm;                  // 32*nf*nwv*nc/2 pixels per tile, padded
   int n_cb;                // c_out / 64
   int tr;                  // global output rows per tile

@@ -199,7 +199,7 @@ __device__ __forceinline__ void mma_granule(const char* __restrict__ pat, const 
   }
 }
 
-template <typename Tr, int NF, int CPS, int PKB, int NWV, int NC>
+template <typename Tr, int NF, int CPS, int PKB, int NWV, int NC, int LDW>
 __global__ __launch_bounds__(NWV * 64, 2) void gated_conv_rows_kernel(
     Params p, Mfma3Plan g, const char* __restrict__ wpk0, const char* __restrict__ wpk1) {
   using acc16 = typename Tr::acc16;
@@ -211,13 +211,19 @@ __global__ __launch_bounds__(NWV * 64, 2) void gated_conv_rows_kernel(
   constexpr int GB = GK * 2048;                // bytes per weight granule
   constexpr int PB = PKB * 1024;               // bytes per patch buffer
   constexpr int SB = 16 * CPS;                 // bytes per pixel slot
-  constexpr int KPW = PB / 1024 / NWV;         // patch load instructions per wavefront per super-stage, at most
+  // LDW > 0: the last LDW wavefronts only issue the LDS-direct loads and the others only multiply
+  // (the loads' issue and bookkeeping instructions then stay out of the MFMA stream); LDW = 0: every
+  // wavefront does both.
+  constexpr int NLW = LDW ? LDW : NWV;         // wavefronts that issue loads
+  constexpr int NCW = NWV - LDW;               // wavefronts that multiply
+  static_assert(LDW == 0 || NC == 2, "loader wavefronts come with full-width compute wavefronts");
+  constexpr int KPW = PB / 1024 / NLW;         // patch load instructions per loading wavefront per super-stage, at most
   constexpr int KH = (KPW + 1) / 2;            // of which in the first granule; the rest in the second
-  constexpr int WPW = (2 * GK + NWV - 1) / NWV;   // weight load instructions per wavefront per granule
+  constexpr int WPW = (2 * GK + NLW - 1) / NLW;   // weight load instructions per loading wavefront per granule
   // NC = 2: a wavefront multiplies its pixels by all 64 channels of the block.  NC = 1: two wavefronts
   // share a pixel fragment, one per 32-channel half (same tile on twice the wavefronts).
   static_assert(NC == 1 || NC == 2, "channel fragments per wavefront");
-  constexpr int NPW = NWV * NC / 2;            // wavefronts across the pixels
+  constexpr int NPW = NCW * NC / 2;            // wavefronts across the pixels
   // K steps the MFMA operands are read ahead (reading three ahead measured no faster on any layer)
   constexpr int PD = 1;
   constexpr int BM = 32 * NF * NPW;            // pixels per tile
@@ -237,6 +243,9 @@ __global__ __launch_bounds__(NWV * 64, 2) void gated_conv_rows_kernel(
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   __builtin_assume(wave >= 0 && wave < NWV);
+  const bool is_cw = wave < NCW;                // this wavefront multiplies
+  const bool is_ld = LDW == 0 || wave >= NCW;   // this wavefront issues loads
+  const int lw = LDW ? wave - NCW : wave;       // its number among the loading wavefronts
   const int pw = wave & (NPW - 1);              // which pixel fragments
   const int fc0 = NC == 2 ? 0 : wave / NPW;     // first 32-channel fragment of this wavefront
   const int lj = lane & 31, lh = lane >> 5;
@@ -274,13 +283,15 @@ __global__ __launch_bounds__(NWV * 64, 2) void gated_conv_rows_kernel(
   // sits at wbase0 + j*GB in the base phase and at wcond0 + (j - 3*S0)*GB in the conditional phase
   const char* const wbase0 = wpk0 + (size_t)cbk * 3 * g.stages[0] * GB;
   const char* const wcond0 = wpk1 + (size_t)cbk * 3 * g.stages[1] * GB;
-  // weight load instruction u of this wavefront: 1 KB number wave + NWV*u of the granule
+  // weight load instruction u of this loading wavefront: 1 KB number lw + NLW*u of the granule
   auto issue_w = [&](const char* ws, char* dst, int u) __attribute__((always_inline)) {
-    const int idx = wave + NWV * u;
+    const int idx = lw + NLW * u;
     if (idx < 2 * GK) lds_direct16(ws + idx * 1024 + lane * 16, dst + idx * 1024);
   };
+  if (is_ld) {
 #pragma unroll
-  for (int u = 0; u < WPW; ++u) issue_w(wbase0, wgt, u);
+    for (int u = 0; u < WPW; ++u) issue_w(wbase0, wgt, u);
+  }
   const char* wnext = wbase0 + GB;   // source of the granule after the one being multiplied
 
   const long long m0 = (long long)R0 * p.wo;        // first output pixel
@@ -290,7 +301,7 @@ __global__ __launch_bounds__(NWV * 64, 2) void gated_conv_rows_kernel(
   const int rho0 = img0 * g.hp + (R0 - img0 * p.ho) * p.stride;   // stacked padded input row of patch row 0
   const int rowb = SB << g.logp;                    // bytes per patch row
 
-  // ---- this wavefront's patch load instructions: instruction idx = wave + NWV*k fills the 64 chunk
+  // ---- a loading wavefront's patch load instructions: instruction idx = lw + NLW*k fills the 64 chunk
   // positions [64*idx, +64), i.e. 64/CPS pixel slots; a lane outside the image keeps a zero that is
   // written once.  smask bit k: the instruction has at least one lane inside the image.
   const char* xbytes = (const char*)p.x;
@@ -300,8 +311,8 @@ __global__ __launch_bounds__(NWV * 64, 2) void gated_conv_rows_kernel(
 #pragma unroll
   for (int k = 0; k < KPW; ++k) {
     voff[k] = -1;
-    const int idx = wave + NWV * k;
-    if (idx < g.ni) {
+    const int idx = lw + NLW * k;
+    if (is_ld && idx < g.ni) {
       const int pos16 = idx * 64 + lane;
       const int sl = pos16 / CPS, cp = pos16 % CPS;
       const int f = CPS == 4 ? (sl >> 2) & 3 : (sl >> 3) & 1;
@@ -343,7 +354,7 @@ __global__ __launch_bounds__(NWV * 64, 2) void gated_conv_rows_kernel(
     const char* xs0 = x_src(0);
 #pragma unroll
     for (int k = 0; k < KPW; ++k)
-      if (((smask >> k) & 1u) && voff[k] >= 0) lds_direct16(xs0 + voff[k], pat2 + (wave + NWV * k) * 1024);
+      if (((smask >> k) & 1u) && voff[k] >= 0) lds_direct16(xs0 + voff[k], pat2 + (lw + NLW * k) * 1024);
   }
 
   // ---- this lane's base-path pixels ------------------------------------------------------------
@@ -354,14 +365,15 @@ __global__ __launch_bounds__(NWV * 64, 2) void gated_conv_rows_kernel(
 #pragma unroll
   for (int fp = 0; fp < NF; ++fp) {
     pix[fp] = (pw * NF + fp) * 32 + lj;
-    pval[fp] = pix[fp] < bmv;
-    const int i = pval[fp] ? pix[fp] : 0;           // fragments past the tile's end read pixel 0 and are dropped
+    const bool inside = pix[fp] < bmv;
+    pval[fp] = is_cw && inside;
+    const int i = inside ? pix[fp] : 0;             // fragments past the tile's end read pixel 0 and are dropped
     const int lr = fdiv3(i, g.magic_wo), wo_ = i - lr * p.wo;
     const int R = R0 + lr;
     const int img = fdiv3(R, g.magic_ho), hq = R - img * p.ho;
     pimg[fp] = img;
     const int slot = ((img * g.hp + hq * p.stride - rho0) << g.logp) + wo_ * p.stride;
-    if (lh == 0) pslot[pix[fp]] = slot;
+    if (lh == 0 && is_cw) pslot[pix[fp]] = slot;
 #pragma unroll
     for (int c = 0; c < 3; ++c) pa[fp][c] = slot_addr<CPS>(slot + c, lh);
   }
@@ -432,6 +444,9 @@ __global__ __launch_bounds__(NWV * 64, 2) void gated_conv_rows_kernel(
     const char* ws = wnext;
     if (gi + 2 < G) wnext = (gi + 2 == 3 * S0) ? wcond0 : wnext + GB;
     auto part = [&](int t) __attribute__((always_inline)) {
+      if constexpr (LDW > 0) {
+        if (NL > 0 || !is_ld) return;      // wavefronts that multiply leave the loads to the loaders
+      }
       constexpr int NU = WPW + NP;
 #pragma unroll
       for (int u = (t * NU) / GK; u < ((t + 1) * NU) / GK; ++u) {
@@ -439,7 +454,7 @@ __global__ __launch_bounds__(NWV * 64, 2) void gated_conv_rows_kernel(
           issue_w(ws, wgn, u);
         } else {
           const int i = u - WPW;
-          if (more && voff[K0 + i] >= 0) lds_direct16(xsn + voff[K0 + i], patn + (wave + NWV * (K0 + i)) * 1024);
+          if (more && voff[K0 + i] >= 0) lds_direct16(xsn + voff[K0 + i], patn + (lw + NLW * (K0 + i)) * 1024);
         }
       }
     };
@@ -453,10 +468,12 @@ __global__ __launch_bounds__(NWV * 64, 2) void gated_conv_rows_kernel(
 #pragma unroll
       for (int c = 0; c < 3; ++c) ar[fp][c] = base[fp][c] + rofs;
     mma_granule<Tr, NL, NF, CPS, NC, PD>(pat, wg, wofs, ar, acc, part);
-    if constexpr (R == 2)
-      wait_vm_upto<0>(0);
-    else
-      wait_vm_upto<NP>(R == 0 ? np0 : np1);
+    if constexpr (LDW == 0 || NL == 0) {     // (a wavefront without loads has nothing to wait for)
+      if constexpr (R == 2)
+        wait_vm_upto<0>(0);
+      else
+        wait_vm_upto<NP>(R == 0 ? np0 : np1);
+    }
   };
   // the three granules of super-stage sg
   auto super_stage = [&](auto nl_tag, acc16 (&acc)[NF][NC], const int (&base)[NF][3], int gi, int sg, bool last)
@@ -473,8 +490,12 @@ __global__ __launch_bounds__(NWV * 64, 2) void gated_conv_rows_kernel(
   // ---- base path --------------------------------------------------------------------------------
   int gi = 0;
 #pragma nounroll
-  for (int sg = 0; sg < S0; ++sg, gi += 3)
-    super_stage(std::integral_constant<int, NF>{}, accP, pa, gi, sg, sg + 1 == S0);
+  for (int sg = 0; sg < S0; ++sg, gi += 3) {
+    if (is_cw)
+      super_stage(std::integral_constant<int, NF>{}, accP, pa, gi, sg, sg + 1 == S0);
+    else
+      super_stage(std::integral_constant<int, 0>{}, accP, pa, gi, sg, sg + 1 == S0);
+  }
 
   if (p.gated) {
     // ---- gate -------------------------------------------------------------------------------
@@ -509,8 +530,8 @@ __global__ __launch_bounds__(NWV * 64, 2) void gated_conv_rows_kernel(
         dl &= ((mw[0] >> (16 * lh)) & 0xffffu) | (((mw[1] >> (16 * lh)) & 0xffffu) << 16);
       }
       dlane[fp] = dl;
-      if (NC == 2 || fc0 == 0) bmph[pix[fp] * 4 + lh] = (uint16_t)(dl & 0xffffu);
-      if (NC == 2 || fc0 == 1) bmph[pix[fp] * 4 + 2 + lh] = (uint16_t)(dl >> 16);
+      if (is_cw && (NC == 2 || fc0 == 0)) bmph[pix[fp] * 4 + lh] = (uint16_t)(dl & 0xffffu);
+      if (is_cw && (NC == 2 || fc0 == 1)) bmph[pix[fp] * 4 + 2 + lh] = (uint16_t)(dl >> 16);
     }
     __syncthreads();
 
@@ -544,7 +565,7 @@ __global__ __launch_bounds__(NWV * 64, 2) void gated_conv_rows_kernel(
 
     // compacted fragment c (32 pixels) goes to the wavefronts of pixel position c % NPW
     const int nc = (n_act + 31) >> 5;
-    nrl = (nc > pw ? 1 : 0) + ((NF == 2 && nc > pw + NPW) ? 1 : 0);
+    nrl = is_cw ? (nc > pw ? 1 : 0) + ((NF == 2 && nc > pw + NPW) ? 1 : 0) : 0;
 #pragma unroll
     for (int k = 0; k < NF; ++k) {
       const int c = (pw + NPW * k) * 32 + lj;
@@ -690,7 +711,7 @@ __global__ __launch_bounds__(NWV * 64, 2) void gated_conv_rows_kernel(
 #pragma unroll
     for (int fp = 0; fp < NF; ++fp) {
       if (fp > 0) __syncthreads();      // the previous fragment's rows have been read
-      {
+      if (is_cw) {
         char* row = pat2 + (pw * 32 + lj) * rs;
 #pragma unroll
         for (int fl = 0; fl < NC; ++fl) {
@@ -832,30 +853,34 @@ __global__ void bitmap_counts_kernel(const uint32_t* __restrict__ bitmap, int wo
   }
 }
 
-template <typename Tr, int NF, int CPS, int PKB, int NWV, int NC>
+template <typename Tr, int NF, int CPS, int PKB, int NWV, int NC, int LDW>
 hipError_t launch_rows_one(const Mfma3Plan& g, const Params& p, const void* w0, const void* w1, hipStream_t s) {
   const long long rows = (long long)p.n * p.ho;
   const long long tiles = (rows + g.tr - 1) / g.tr;
   const long long blocks = ((tiles + 7) / 8) * 8 * g.n_cb;
   if (blocks <= 0) return hipSuccess;
   if (blocks > 0x7fffffffll) return hipErrorInvalidValue;
-  auto kern = gated_conv_rows_kernel<Tr, NF, CPS, PKB, NWV, NC>;
+  auto kern = gated_conv_rows_kernel<Tr, NF, CPS, PKB, NWV, NC, LDW>;
   hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(NWV * 64), 0, s, p, g, (const char*)w0, (const char*)w1);
   return hipGetLastError();
 }
 
 template <typename Tr, int NF, int CPS>
 hipError_t launch_rows_cps(const Mfma3Plan& g, const Params& p, const void* w0, const void* w1, hipStream_t s) {
+  if (g.ldw == 4) {
+    if (g.pkb == 24) return launch_rows_one<Tr, NF, CPS, 24, 8, 2, 4>(g, p, w0, w1, s);
+    return launch_rows_one<Tr, NF, CPS, 48, 8, 2, 4>(g, p, w0, w1, s);
+  }
   if (g.nwv == 8 && g.nc == 2) {
-    if (g.pkb == 24) return launch_rows_one<Tr, NF, CPS, 24, 8, 2>(g, p, w0, w1, s);
-    return launch_rows_one<Tr, NF, CPS, 48, 8, 2>(g, p, w0, w1, s);
+    if (g.pkb == 24) return launch_rows_one<Tr, NF, CPS, 24, 8, 2, 0>(g, p, w0, w1, s);
+    return launch_rows_one<Tr, NF, CPS, 48, 8, 2, 0>(g, p, w0, w1, s);
   }
   if (g.nwv == 8) {
-    if (g.pkb == 24) return launch_rows_one<Tr, NF, CPS, 24, 8, 1>(g, p, w0, w1, s);
-    return launch_rows_one<Tr, NF, CPS, 48, 8, 1>(g, p, w0, w1, s);
+    if (g.pkb == 24) return launch_rows_one<Tr, NF, CPS, 24, 8, 1, 0>(g, p, w0, w1, s);
+    return launch_rows_one<Tr, NF, CPS, 48, 8, 1, 0>(g, p, w0, w1, s);
   }
-  if (g.pkb == 24) return launch_rows_one<Tr, NF, CPS, 24, 4, 2>(g, p, w0, w1, s);
-  return launch_rows_one<Tr, NF, CPS, 48, 4, 2>(g, p, w0, w1, s);
+  if (g.pkb == 24) return launch_rows_one<Tr, NF, CPS, 24, 4, 2, 0>(g, p, w0, w1, s);
+  return launch_rows_one<Tr, NF, CPS, 48, 4, 2, 0>(g, p, w0, w1, s);
 }
 
 template <typename Tr>
@@ -964,7 +989,16 @@ Mfma3Plan mfma3_plan(const cg_conv_desc& d) {
       g.nwv = c.nwv;
       g.nf = nf;
       g.nc = 2;
-      if (nf == 1 && c.pkb == 48) {
+      g.ldw = 0;
+      {
+        const char* e = getenv("CG_MFMA3_LDW");
+        const int mode = e ? atoi(e) : 0;
+        if (nf == 1 && (mode == 1 || (mode == 2 && c.pkb == 24))) {
+          g.nwv = 8;
+          g.ldw = 4;
+        }
+      }
+      if (nf == 1 && c.pkb == 48 && g.ldw == 0) {
         // a tile that is alone on its CU (large patch buffers): eight wavefronts, two per pixel
         // fragment with 32 channels each, measured 5-10 % faster there than four with 64
         g.nwv = 8;
