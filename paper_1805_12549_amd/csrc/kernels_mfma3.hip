@@ -990,13 +990,12 @@ Mfma3Plan mfma3_plan(const cg_conv_desc& d) {
       g.nf = nf;
       g.nc = 2;
       g.ldw = 0;
-      {
-        const char* e = getenv("CG_MFMA3_LDW");
-        const int mode = e ? atoi(e) : 0;
-        if (nf == 1 && (mode == 1 || (mode == 2 && c.pkb == 24))) {
-          g.nwv = 8;
-          g.ldw = 4;
-        }
+      if (nf == 1 && c.pkb == 24 && tiles * g.n_cb <= 256) {
+        // a small tile that is alone on its CU because the grid has no second one to offer: four
+        // more wavefronts take over the LDS-direct loads (measured 5-8 % faster on the 512-channel
+        // 7x7 layer; slower where two workgroups share a CU)
+        g.nwv = 8;
+        g.ldw = 4;
       }
       if (nf == 1 && c.pkb == 48 && g.ldw == 0) {
         // a tile that is alone on its CU (large patch buffers): eight wavefronts, two per pixel
