@@ -19,10 +19,22 @@ def summarize(db_path: str, command: str = "") -> str:
         out.append("command: " + command)
     out.append("source: rocprofv3 --kernel-trace --stats (durations in microseconds)")
     out.append("%-9s %-12s %-10s %-10s %-10s %-6s %s" % ("calls", "total_us", "avg_us", "min_us", "max_us", "pct", "kernel"))
+    def shorten(name):
+        name = name.replace("cg::(anonymous namespace)::", "").replace("void ", "")
+        cut = name.find(">(")
+        name = name[:cut + 1] if cut > 0 else name
+        return name if len(name) < 110 else name[:107] + "..."
+
     for name, calls, tot, avg, mn, mx in rows[:12]:
-        short = name if len(name) < 110 else name[:107] + "..."
         out.append("%-9d %-12.1f %-10.2f %-10.2f %-10.2f %-6.2f %s" % (
-            calls, tot / 1e3, avg / 1e3, mn / 1e3, mx / 1e3, 100.0 * tot / total, short))
+            calls, tot / 1e3, avg / 1e3, mn / 1e3, mx / 1e3, 100.0 * tot / total, shorten(name)))
+    # all instantiations of the layer kernel together (the figure bench.py's avg_launch_us reports)
+    fam = [r for r in rows if "gated_conv_rows_kernel" in r[0]]
+    if fam:
+        calls = sum(r[1] for r in fam)
+        tot = sum(r[2] for r in fam)
+        out.append("")
+        out.append("gated_conv_rows_kernel, all instantiations: %d calls, average %.2f us" % (calls, tot / calls / 1e3))
     # per-grid breakdown of the dominant kernel (one line per layer shape)
     if rows:
         dom = rows[0][0]
@@ -63,6 +75,13 @@ def traffic(fetch_csv: str, write_csv: str, copy_bytes: int = 256 << 20, kernel:
         out.append("%-8d %-14.0f %-14.0f %-14.0f" % (i, fb, wb, fb + wb))
     n = max(1, min(len(f_layer), len(w_layer)))
     out.append("bytes_per_launch: %.0f" % (tot / n))
+    out += ["commands (each in its own run, after cd /tmp && export TMPDIR=/tmp, from the repository root):",
+            "  rocprofv3 --pmc FETCH_SIZE --output-format csv -d gpurun_out/prof_fetch -o r -- python3 -m paper_1805_12549_amd.traffic_probe",
+            "  rocprofv3 --pmc WRITE_SIZE --output-format csv -d gpurun_out/prof_write -o r -- python3 -m paper_1805_12549_amd.traffic_probe",
+            "  python -m paper_1805_12549_amd.profile_summary --traffic gpurun_out/prof_fetch/r_counter_collection.csv "
+            "gpurun_out/prof_write/r_counter_collection.csv",
+            "launches 0..6 = the 7 ImageNet-shaped ResNet-18 gated 3x3 layers (64@56, 128@28, 256@14, 512@7, 64>128 s2, "
+            "128>256 s2, 256>512 s2), batch 64, bf16, one cold-cache forward each"]
     return "\n".join(out) + "\n"
 
 
