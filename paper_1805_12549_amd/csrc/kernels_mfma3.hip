@@ -1,9 +1,11 @@
 // Row-tiled matrix-core kernel of the gated convolution (bf16 and int8 MFMA, 32x32 blocks).
 //
-// One workgroup of four or eight wavefronts owns BM = 32*NF pixels per wavefront of consecutive
-// output pixels (whole output rows of the batch, numbered R = img*Ho + ho, possibly straddling
-// images) times 64 output channels and runs the whole layer for them (Eq. 1 of the channel-gating
-// paper).  Eight-wavefront workgroups own a CU; four-wavefront ones share it two or three at a time.
+// One workgroup of four or eight wavefronts owns a tile of 128 or 256 consecutive output pixels
+// (whole output rows of the batch, numbered R = img*Ho + ho, possibly straddling images) times 64
+// output channels and runs the whole layer for them (Eq. 1 of the channel-gating paper).  A
+// wavefront multiplies NF 32-pixel fragments by the block's 64 channels; in the channel-split form
+// (NC = 1) two wavefronts share a fragment with 32 channels each; in the loader form (LDW = 4) four
+// extra wavefronts only issue the loads.  Two workgroups share a CU where LDS allows.
 //
 //   base path   implicit GEMM over taps x base channels.  Each wavefront owns NF 32-pixel
 //               fragments x 64 channels.  The product is taken transposed (weights as the row
@@ -28,11 +30,11 @@
 // f(s) = (s >> 2) & 3 (CPS = 4) or (s >> 3) & 1 (CPS = 2), which makes the 16-lane operand reads
 // conflict-free.  Slot = patch_row * P + c with P a power of two >= max(16, W + pad) and
 // c = wi + pad, so the zero padding left and right of a row are the never-loaded slots between
-// rows; rows outside the image are zeroed once.  Weights stream through a ring of granules, one
-// kernel row (three taps) of the super-stage each: two deep for four wavefronts, four deep (fetched
-// three granules ahead) for eight; the granule fetch and a part of the next super-stage's patch go
-// out as LDS-direct loads while a granule is multiplied, and the wait at the granule's end covers
-// only what the next granule needs (the loads of a wavefront complete in order).
+// rows; rows outside the image are zeroed once.  Weights stream through a two-deep ring of granules,
+// one kernel row (three taps) of the super-stage each; the next granule's fetch and a part of the
+// next super-stage's patch go out as LDS-direct loads while a granule is multiplied, and the wait at
+// the granule's end covers only what the next granule needs (the loads of a wavefront complete in
+// order).
 #include <cstdlib>
 #include <type_traits>
 #include <utility>

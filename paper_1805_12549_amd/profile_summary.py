@@ -1,7 +1,7 @@
 """Turn a rocprofv3 ``*_results.db`` (rocpd SQLite output of ``--kernel-trace --stats``) into
 the short per-kernel text table kept under ``profiles/``.
 
-    python -m paper_1805_12549_amd.profile_summary gpurun_out/prof/run_results.db "command line" > profiles/x.txt
+    python -m paper_1805_12549_amd.profile_summary <out-dir>/run_results.db "command line" > profiles/x.txt
 """
 import sqlite3
 import sys
