@@ -220,3 +220,53 @@ def forward_int8(x, w_base, w_cond, thr, *, stride=1, pad=1, out_i8=False, rq_mu
     out["macs"] = int(macs.value)
     out["fired"] = int(out["counts"][0]) | (int(out["counts"][1]) << 32)
     return out
+
+
+# ----------------------------------------------------------------------------
+# dense pieces of a ResNet around the gated layers (plain definitions in cg_ref.c)
+# ----------------------------------------------------------------------------
+
+def dense_conv(x, w, *, stride=1, pad=0, scale=None, shift=None, relu=False):
+    """x [N,H,W,C_in], w [C_out,k,k,C_in] -> [N,Ho,Wo,C_out] float64."""
+    lib = _load()
+    x, w = _as(x, np.float64), _as(w, np.float64)
+    n, h, wd, c_in = x.shape
+    c_out, k = w.shape[0], w.shape[1]
+    assert w.shape == (c_out, k, k, c_in)
+    scale, shift = _as(scale, np.float64), _as(shift, np.float64)
+    ho, wo = out_hw(h, wd, k, k, stride, pad)
+    y = np.empty((n, ho, wo, c_out))
+    lib.cg_ref_dense_conv.argtypes = [_pd, _pd, _pd, _pd, _pd] + [C.c_int] * 9
+    rc = lib.cg_ref_dense_conv(_ptr(x, _pd), _ptr(w, _pd), _ptr(scale, _pd), _ptr(shift, _pd), _ptr(y, _pd),
+                               n, h, wd, c_in, c_out, k, stride, pad, int(bool(relu)))
+    if rc != 0:
+        raise ValueError("cg_ref_dense_conv rejected the problem")
+    return y
+
+
+def maxpool3x3s2(x):
+    """x [N,H,W,C] -> [N,(H-1)//2+1,(W-1)//2+1,C] float64 (padding 1)."""
+    lib = _load()
+    x = _as(x, np.float64)
+    n, h, wd, c = x.shape
+    ho, wo = out_hw(h, wd, 3, 3, 2, 1)
+    y = np.empty((n, ho, wo, c))
+    lib.cg_ref_maxpool3x3s2.argtypes = [_pd, _pd] + [C.c_int] * 4
+    if lib.cg_ref_maxpool3x3s2(_ptr(x, _pd), _ptr(y, _pd), n, h, wd, c) != 0:
+        raise ValueError("cg_ref_maxpool3x3s2 rejected the problem")
+    return y
+
+
+def avgpool_fc(x, wfc, bias=None):
+    """x [N,HW,C] (or [N,H,W,C]), wfc [classes,C] -> logits [N,classes] float64."""
+    lib = _load()
+    x, wfc, bias = _as(x, np.float64), _as(wfc, np.float64), _as(bias, np.float64)
+    n, c = x.shape[0], x.shape[-1]
+    hw = int(np.prod(x.shape[1:-1]))
+    classes = wfc.shape[0]
+    assert wfc.shape == (classes, c)
+    out = np.empty((n, classes))
+    lib.cg_ref_avgpool_fc.argtypes = [_pd, _pd, _pd, _pd] + [C.c_int] * 4
+    if lib.cg_ref_avgpool_fc(_ptr(x, _pd), _ptr(wfc, _pd), _ptr(bias, _pd), _ptr(out, _pd), n, hw, c, classes) != 0:
+        raise ValueError("cg_ref_avgpool_fc rejected the problem")
+    return out

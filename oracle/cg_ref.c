@@ -339,3 +339,79 @@ int cg_ref_forward(const cg_ref_problem *p) {
   if (p->macs) *p->macs = total_macs;
   return 0;
 }
+
+/*
+ * The dense pieces of a ResNet around the gated layers (the paper's experiments
+ * run ResNet-18, Sec. 5), as plain definitions in double precision, NHWC.
+ */
+
+/* y[n][ho][wo][co] = relu?(scale[co] * sum_{r,s,c} x[n][ho*st-pad+r][wo*st-pad+s][c] * w[co][r][s][c] + shift[co]),
+ * taps outside the image contribute nothing; scale / shift may be NULL (1 / 0). */
+int cg_ref_dense_conv(const double *x, const double *w, const double *scale, const double *shift, double *y, int n,
+                      int h, int wd, int c_in, int c_out, int k, int stride, int pad, int relu) {
+  if (!x || !w || !y || n < 0 || h <= 0 || wd <= 0 || c_in <= 0 || c_out <= 0 || k <= 0 || stride <= 0 || pad < 0)
+    return 1;
+  const int ho = out_size(h, k, stride, pad), wo = out_size(wd, k, stride, pad);
+#pragma omp parallel for collapse(2) schedule(static)
+  for (int i = 0; i < n; ++i)
+    for (int oy = 0; oy < ho; ++oy)
+      for (int ox = 0; ox < wo; ++ox)
+        for (int co = 0; co < c_out; ++co) {
+          double acc = 0.0;
+          for (int r = 0; r < k; ++r) {
+            const int hi = oy * stride - pad + r;
+            if (hi < 0 || hi >= h) continue;
+            for (int s = 0; s < k; ++s) {
+              const int wi = ox * stride - pad + s;
+              if (wi < 0 || wi >= wd) continue;
+              for (int c = 0; c < c_in; ++c)
+                acc += x[(((size_t)i * h + hi) * wd + wi) * c_in + c] * w[(((size_t)co * k + r) * k + s) * c_in + c];
+            }
+          }
+          double a = (scale ? scale[co] : 1.0) * acc + (shift ? shift[co] : 0.0);
+          if (relu && a < 0.0) a = 0.0;
+          y[(((size_t)i * ho + oy) * wo + ox) * c_out + co] = a;
+        }
+  return 0;
+}
+
+/* 3x3 max pooling, stride 2, padding 1: the maximum over the taps inside the image. */
+int cg_ref_maxpool3x3s2(const double *x, double *y, int n, int h, int wd, int c) {
+  if (!x || !y || n < 0 || h <= 0 || wd <= 0 || c <= 0) return 1;
+  const int ho = out_size(h, 3, 2, 1), wo = out_size(wd, 3, 2, 1);
+  for (int i = 0; i < n; ++i)
+    for (int oy = 0; oy < ho; ++oy)
+      for (int ox = 0; ox < wo; ++ox)
+        for (int ch = 0; ch < c; ++ch) {
+          double m = -INFINITY;
+          for (int r = 0; r < 3; ++r) {
+            const int hi = oy * 2 - 1 + r;
+            if (hi < 0 || hi >= h) continue;
+            for (int s = 0; s < 3; ++s) {
+              const int wi = ox * 2 - 1 + s;
+              if (wi < 0 || wi >= wd) continue;
+              const double v = x[(((size_t)i * h + hi) * wd + wi) * c + ch];
+              if (v > m) m = v;
+            }
+          }
+          y[(((size_t)i * ho + oy) * wo + ox) * c + ch] = m;
+        }
+  return 0;
+}
+
+/* logits[n][k] = sum_c wfc[k][c] * mean_p x[n][p][c] + bias[k] */
+int cg_ref_avgpool_fc(const double *x, const double *wfc, const double *bias, double *logits, int n, int hw, int c,
+                      int classes) {
+  if (!x || !wfc || !logits || n < 0 || hw <= 0 || c <= 0 || classes <= 0) return 1;
+  for (int i = 0; i < n; ++i)
+    for (int k = 0; k < classes; ++k) {
+      double s = 0.0;
+      for (int ch = 0; ch < c; ++ch) {
+        double m = 0.0;
+        for (int p = 0; p < hw; ++p) m += x[((size_t)i * hw + p) * c + ch];
+        s += wfc[(size_t)k * c + ch] * (m / hw);
+      }
+      logits[(size_t)i * classes + k] = s + (bias ? bias[k] : 0.0);
+    }
+  return 0;
+}

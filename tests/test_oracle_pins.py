@@ -596,3 +596,42 @@ def test_channel_gate_extremes_and_nesting():
         prev = cur["d"]
         sums.append(int(prev.sum()))
     assert any(0 < v < int(off["d"].sum()) for v in sums)
+
+
+# ---------------------------------------------------------------------------
+# Dense pieces of a ResNet around the gated layers: library routines and hand values
+# ---------------------------------------------------------------------------
+@pytest.mark.parametrize("k,stride,pad,c_in", [(7, 2, 3, 3), (3, 1, 1, 4), (5, 2, 2, 1), (1, 2, 0, 8)])
+def test_dense_conv_matches_library(k, stride, pad, c_in):
+    rng = np.random.default_rng(k * 10 + stride)
+    x = rng.standard_normal((2, 13, 11, c_in))
+    w = rng.standard_normal((6, k, k, c_in)) * 0.2
+    sc, sh = rng.uniform(0.5, 1.5, 6), rng.standard_normal(6) * 0.1
+    got = O.dense_conv(x, w, stride=stride, pad=pad, scale=sc, shift=sh, relu=True)
+    want = np.maximum(lib_conv(x, w, stride, pad) * sc + sh, 0)
+    np.testing.assert_allclose(got, want, rtol=1e-12, atol=1e-12)
+    np.testing.assert_allclose(O.dense_conv(x, w, stride=stride, pad=pad), lib_conv(x, w, stride, pad), rtol=1e-12, atol=1e-12)
+
+
+def test_maxpool_matches_library_and_ignores_padding():
+    rng = np.random.default_rng(8)
+    for h, w in ((8, 8), (7, 9), (5, 4), (1, 1)):
+        x = rng.standard_normal((2, h, w, 5)) - 3.0          # all negative: zero padding would win if it counted
+        want = torch.nn.functional.max_pool2d(torch.from_numpy(x).permute(0, 3, 1, 2), 3, 2, 1).permute(0, 2, 3, 1).numpy()
+        got = O.maxpool3x3s2(x)
+        assert got.shape == want.shape == (2, (h - 1) // 2 + 1, (w - 1) // 2 + 1, 5)
+        np.testing.assert_array_equal(got, want)
+    # by hand: 4x4 ramp, output (0,0) sees rows/cols {0,1}, output (1,1) sees rows/cols {1,2,3}
+    x = np.arange(16, dtype=np.float64).reshape(1, 4, 4, 1)
+    np.testing.assert_array_equal(O.maxpool3x3s2(x)[0, :, :, 0], [[5, 7], [13, 15]])
+
+
+def test_avgpool_fc_matches_library():
+    rng = np.random.default_rng(9)
+    x = rng.standard_normal((3, 7, 7, 10))
+    w, b = rng.standard_normal((4, 10)), rng.standard_normal(4)
+    want = x.mean(axis=(1, 2)) @ w.T + b
+    np.testing.assert_allclose(O.avgpool_fc(x, w, b), want, rtol=1e-12, atol=1e-12)
+    np.testing.assert_allclose(O.avgpool_fc(x.reshape(3, 49, 10), w), want - b, rtol=1e-12, atol=1e-12)
+    # by hand: constant maps, identity weights
+    np.testing.assert_allclose(O.avgpool_fc(np.full((1, 4, 2), 3.0), np.eye(2)), [[3.0, 3.0]])
