@@ -170,6 +170,31 @@ int cg_conv_info(const cg_conv* h, int32_t* ho, int32_t* wo);
 /* Text of the calling thread's most recent error; never NULL. */
 const char* cg_last_error(void);
 
+/*
+ * The dense pieces of a ResNet around the gated layers (the paper's experiments, Sec. 5, run
+ * ResNet-18): none of them is gated.  bf16 activations and weights (NHWC / [c_out][k][k][c_in]),
+ * fp32 accumulation, all pointers DEVICE, nothing allocated, work only enqueued on hip_stream.
+ * Each returns CG_OK or an error code with text in cg_last_error(); arguments are checked before
+ * any HIP call.  (A 1x1 stride-2 shortcut convolution is a dense layer of cg_conv_create:
+ * kh = kw = 1, c_base == c_in.)
+ */
+
+/* Convolution on few input channels (the 7x7 stride-2 input layer): c_in in [1,4], c_out a multiple of
+ * 64, k odd <= 7, stride 1|2, zero padding pad < k.  y[n][ho][wo][c_out] = relu?(scale*conv + shift);
+ * scale / shift: [c_out] floats, nullable (= 1 / 0).  y 16-byte aligned. */
+int cg_small_cin_conv(const void* x, const void* w, const float* scale, const float* shift, void* y, int32_t n,
+                      int32_t h, int32_t wd, int32_t c_in, int32_t c_out, int32_t k, int32_t stride, int32_t pad,
+                      int32_t relu, void* hip_stream);
+
+/* 3x3 max pooling, stride 2, padding 1 (the maximum runs over the taps inside the image):
+ * x[n][h][w][c] -> y[n][(h-1)/2+1][(w-1)/2+1][c]; c a multiple of 8; x, y 16-byte aligned. */
+int cg_maxpool3x3s2(const void* x, void* y, int32_t n, int32_t h, int32_t wd, int32_t c, void* hip_stream);
+
+/* Global average pooling over the hw positions of x[n][hw][c], then the fully connected layer:
+ * logits[n][classes] (fp32) = wfc[classes][c] * mean + bias (bias nullable). */
+int cg_avgpool_fc(const void* x, const void* wfc, const float* bias, float* logits, int32_t n, int32_t hw, int32_t c,
+                  int32_t classes, void* hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -11,7 +11,7 @@ ROOT = PKG.parent
 CSRC = PKG / "csrc"
 LIB = PKG / "libcg_conv.so"
 
-SOURCES = ["cg_conv_api.hip", "kernels_naive.hip", "kernels_mfma.hip", "kernels_mfma2.hip", "kernels_mfma3.hip"]
+SOURCES = ["cg_conv_api.hip", "kernels_naive.hip", "kernels_mfma.hip", "kernels_mfma2.hip", "kernels_mfma3.hip", "kernels_dense.hip"]
 
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",

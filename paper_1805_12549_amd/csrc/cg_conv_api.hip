@@ -28,6 +28,22 @@ int fail(int code, const char* fmt, ...) {
 }
 
 size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
+}  // namespace
+
+namespace cg {
+// records the calling thread's error text for cg_last_error(); returns `code`
+int set_error(int code, const char* fmt, ...) {
+  char buf[512];
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(buf, sizeof buf, fmt, ap);
+  va_end(ap);
+  g_err = buf;
+  return code;
+}
+}  // namespace cg
+
+namespace {
 
 int elem_bytes(int dtype) {
   switch (dtype) {

@@ -1,0 +1,235 @@
+// The dense pieces of a ResNet around the gated layers (the paper evaluates ResNet-18, Sec. 5):
+// the input convolution on few channels (7x7 stride 2 on RGB), 3x3 stride-2 max pooling and global
+// average pooling followed by the fully connected layer.  None of them is gated.  bf16 activations
+// and weights, fp32 accumulation.  (The 1x1 stride-2 shortcut convolutions run through
+// cg_conv_create / cg_conv_forward as dense layers, c_base == c_in.)
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+
+#include "cg_device.h"
+
+namespace cg {
+int set_error(int code, const char* fmt, ...);   // defined with the host API
+}
+
+namespace {
+
+using cg::bf16_to_float;
+using cg::float_to_bf16;
+
+constexpr int kTile = 8;      // output pixels per block edge
+constexpr int kCb = 64;       // output channels per block
+constexpr int kMaxTaps = 7 * 7 * 4;
+
+// Direct convolution for c_in <= 4.  Block = 8x8 output pixels x 64 output channels, 256 threads:
+// thread (px, g) accumulates channels [16g, 16g+16) of pixel px.  A wavefront holds one g and 64
+// pixels, so its weight reads are LDS broadcasts and its input reads are one word per lane.
+__global__ __launch_bounds__(256) void small_cin_conv_kernel(const uint16_t* __restrict__ x,
+                                                             const uint16_t* __restrict__ w,
+                                                             const float* __restrict__ scale,
+                                                             const float* __restrict__ shift, uint16_t* __restrict__ y,
+                                                             int n, int h, int wd, int c_in, int c_out, int k, int stride,
+                                                             int pad, int ho, int wo, int relu) {
+  extern __shared__ float lds[];
+  const int taps = k * k * c_in;
+  float* wl = lds;                          // [taps][64]
+  const int pe = (kTile - 1) * stride + k;  // patch edge
+  float* xl = lds + taps * kCb;             // [pe][pe][c_in]
+  const int tid = threadIdx.x;
+  const int tiles_w = (wo + kTile - 1) / kTile, tiles_h = (ho + kTile - 1) / kTile;
+  int b = blockIdx.x;
+  const int tw = b % tiles_w;
+  b /= tiles_w;
+  const int th = b % tiles_h;
+  const int img = b / tiles_h;
+  const int cb = blockIdx.y;
+
+  // weights of this channel block: caller layout [c_out][k][k][c_in] -> [tap][channel]
+  for (int i = tid; i < taps * kCb; i += 256) {
+    const int co = i / taps, t = i - co * taps;
+    wl[t * kCb + co] = bf16_to_float(w[(long long)(cb * kCb + co) * taps + t]);
+  }
+  // input patch, zero outside the image
+  const int h0 = th * kTile * stride - pad, w0 = tw * kTile * stride - pad;
+  for (int i = tid; i < pe * pe * c_in; i += 256) {
+    const int c = i % c_in, q = i / c_in;
+    const int pw = q % pe, ph = q / pe;
+    const int hi = h0 + ph, wi = w0 + pw;
+    float v = 0.0f;
+    if (hi >= 0 && hi < h && wi >= 0 && wi < wd) v = bf16_to_float(x[(((long long)img * h + hi) * wd + wi) * c_in + c]);
+    xl[i] = v;
+  }
+  __syncthreads();
+
+  const int px = tid & 63, g = tid >> 6;
+  const int oh = px / kTile, ow = px % kTile;
+  float acc[16];
+#pragma unroll
+  for (int i = 0; i < 16; ++i) acc[i] = 0.0f;
+  const float* xp = xl + ((oh * stride) * pe + ow * stride) * c_in;
+  const int row_taps = k * c_in;            // contiguous taps of one kernel row
+  for (int r = 0; r < k; ++r) {
+    const float* xr = xp + r * pe * c_in;
+    const float* wr = wl + (r * row_taps) * kCb + g * 16;
+    for (int t = 0; t < row_taps; ++t) {
+      const float xv = xr[t];
+      const float4 w0v = *(const float4*)(wr + t * kCb);
+      const float4 w1v = *(const float4*)(wr + t * kCb + 4);
+      const float4 w2v = *(const float4*)(wr + t * kCb + 8);
+      const float4 w3v = *(const float4*)(wr + t * kCb + 12);
+      acc[0] = fmaf(xv, w0v.x, acc[0]);
+      acc[1] = fmaf(xv, w0v.y, acc[1]);
+      acc[2] = fmaf(xv, w0v.z, acc[2]);
+      acc[3] = fmaf(xv, w0v.w, acc[3]);
+      acc[4] = fmaf(xv, w1v.x, acc[4]);
+      acc[5] = fmaf(xv, w1v.y, acc[5]);
+      acc[6] = fmaf(xv, w1v.z, acc[6]);
+      acc[7] = fmaf(xv, w1v.w, acc[7]);
+      acc[8] = fmaf(xv, w2v.x, acc[8]);
+      acc[9] = fmaf(xv, w2v.y, acc[9]);
+      acc[10] = fmaf(xv, w2v.z, acc[10]);
+      acc[11] = fmaf(xv, w2v.w, acc[11]);
+      acc[12] = fmaf(xv, w3v.x, acc[12]);
+      acc[13] = fmaf(xv, w3v.y, acc[13]);
+      acc[14] = fmaf(xv, w3v.z, acc[14]);
+      acc[15] = fmaf(xv, w3v.w, acc[15]);
+    }
+  }
+  const int oy = th * kTile + oh, ox = tw * kTile + ow;
+  if (oy < ho && ox < wo) {
+    const int co0 = cb * kCb + g * 16;
+    uint16_t out[16];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      float a = acc[i];
+      if (scale) a *= scale[co0 + i];
+      if (shift) a += shift[co0 + i];
+      if (relu) a = fmaxf(a, 0.0f);
+      out[i] = float_to_bf16(a);
+    }
+    uint4* dst = (uint4*)(y + (((long long)img * ho + oy) * wo + ox) * c_out + co0);
+    dst[0] = *(const uint4*)(out);
+    dst[1] = *(const uint4*)(out + 8);
+  }
+}
+
+// 3x3 stride-2 max pooling with padding 1: the maximum over the taps inside the image.
+// One thread per (output pixel, 8 channels).
+__global__ __launch_bounds__(256) void maxpool3x3s2_kernel(const uint16_t* __restrict__ x, uint16_t* __restrict__ y, int n,
+                                                           int h, int wd, int c, int ho, int wo) {
+  const long long t = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  const int c8 = c >> 3;
+  const long long total = (long long)n * ho * wo * c8;
+  if (t >= total) return;
+  const int cc = (int)(t % c8);
+  long long q = t / c8;
+  const int ox = (int)(q % wo);
+  q /= wo;
+  const int oy = (int)(q % ho);
+  const int img = (int)(q / ho);
+  float m[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) m[i] = -__builtin_inff();
+  for (int r = 0; r < 3; ++r) {
+    const int hi = oy * 2 - 1 + r;
+    if (hi < 0 || hi >= h) continue;
+    for (int s = 0; s < 3; ++s) {
+      const int wi = ox * 2 - 1 + s;
+      if (wi < 0 || wi >= wd) continue;
+      uint16_t v[8];
+      *(uint4*)v = *(const uint4*)(x + (((long long)img * h + hi) * wd + wi) * c + cc * 8);
+#pragma unroll
+      for (int i = 0; i < 8; ++i) m[i] = fmaxf(m[i], bf16_to_float(v[i]));
+    }
+  }
+  uint16_t out[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) out[i] = float_to_bf16(m[i]);
+  *(uint4*)(y + (((long long)img * ho + oy) * wo + ox) * c + cc * 8) = *(const uint4*)out;
+}
+
+// Global average pooling over hw positions, then logits = W * mean + bias.  One block per image.
+__global__ __launch_bounds__(256) void avgpool_fc_kernel(const uint16_t* __restrict__ x, const uint16_t* __restrict__ wfc,
+                                                         const float* __restrict__ bias, float* __restrict__ logits,
+                                                         int hw, int c, int classes) {
+  extern __shared__ float mean[];
+  const int img = blockIdx.x;
+  const float inv = 1.0f / (float)hw;
+  for (int ch = threadIdx.x; ch < c; ch += blockDim.x) {
+    float s = 0.0f;
+    for (int p = 0; p < hw; ++p) s += bf16_to_float(x[((long long)img * hw + p) * c + ch]);
+    mean[ch] = s * inv;
+  }
+  __syncthreads();
+  // one wavefront per class: lanes stride over the channels, then a butterfly sum
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
+  for (int k = wave; k < classes; k += nw) {
+    float s = 0.0f;
+    for (int ch = lane; ch < c; ch += 64) s = fmaf(bf16_to_float(wfc[(long long)k * c + ch]), mean[ch], s);
+#pragma unroll
+    for (int sft = 32; sft >= 1; sft >>= 1) s += __shfl_xor(s, sft, 64);
+    if (lane == 0) logits[(long long)img * classes + k] = s + (bias ? bias[k] : 0.0f);
+  }
+}
+
+}  // namespace
+
+extern "C" {
+
+int cg_small_cin_conv(const void* x, const void* w, const float* scale, const float* shift, void* y, int32_t n,
+                      int32_t h, int32_t wd, int32_t c_in, int32_t c_out, int32_t k, int32_t stride, int32_t pad,
+                      int32_t relu, void* hip_stream) {
+  if (!x || !w || !y) return cg::set_error(CG_EINVAL, "cg_small_cin_conv: x, w and y must not be NULL");
+  if (n < 0 || h <= 0 || wd <= 0) return cg::set_error(CG_EINVAL, "cg_small_cin_conv: bad image size");
+  if (c_in < 1 || c_in > 4) return cg::set_error(CG_EUNSUPPORTED, "cg_small_cin_conv: c_in must lie in [1, 4]");
+  if (c_out <= 0 || c_out % kCb) return cg::set_error(CG_EUNSUPPORTED, "cg_small_cin_conv: c_out must be a multiple of 64");
+  if (k < 1 || k > 7 || !(k & 1)) return cg::set_error(CG_EUNSUPPORTED, "cg_small_cin_conv: kernel size must be odd, at most 7");
+  if (stride < 1 || stride > 2 || pad < 0 || pad >= k) return cg::set_error(CG_EINVAL, "cg_small_cin_conv: bad stride or pad");
+  if (h + 2 * pad < k || wd + 2 * pad < k) return cg::set_error(CG_EINVAL, "cg_small_cin_conv: kernel larger than the padded input");
+  if ((((uintptr_t)y) & 15) != 0) return cg::set_error(CG_EINVAL, "cg_small_cin_conv: y must be 16-byte aligned");
+  if (n == 0) return CG_OK;
+  const int ho = (h + 2 * pad - k) / stride + 1, wo = (wd + 2 * pad - k) / stride + 1;
+  const long long tiles = (long long)n * ((ho + kTile - 1) / kTile) * ((wo + kTile - 1) / kTile);
+  if (tiles > 0x7fffffffll) return cg::set_error(CG_EUNSUPPORTED, "cg_small_cin_conv: too many tiles");
+  const int pe = (kTile - 1) * stride + k;
+  const size_t lds = ((size_t)k * k * c_in * kCb + (size_t)pe * pe * c_in) * sizeof(float);
+  hipLaunchKernelGGL(small_cin_conv_kernel, dim3((unsigned)tiles, (unsigned)(c_out / kCb)), dim3(256), lds,
+                     (hipStream_t)hip_stream, (const uint16_t*)x, (const uint16_t*)w, scale, shift, (uint16_t*)y, n, h, wd,
+                     c_in, c_out, k, stride, pad, ho, wo, relu);
+  const hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return cg::set_error(CG_EHIP, "cg_small_cin_conv: %s", hipGetErrorString(e));
+  return CG_OK;
+}
+
+int cg_maxpool3x3s2(const void* x, void* y, int32_t n, int32_t h, int32_t wd, int32_t c, void* hip_stream) {
+  if (!x || !y) return cg::set_error(CG_EINVAL, "cg_maxpool3x3s2: x and y must not be NULL");
+  if (n < 0 || h <= 0 || wd <= 0 || c <= 0) return cg::set_error(CG_EINVAL, "cg_maxpool3x3s2: bad size");
+  if (c % 8) return cg::set_error(CG_EUNSUPPORTED, "cg_maxpool3x3s2: c must be a multiple of 8");
+  if ((((uintptr_t)x) | ((uintptr_t)y)) & 15) return cg::set_error(CG_EINVAL, "cg_maxpool3x3s2: x and y must be 16-byte aligned");
+  if (n == 0) return CG_OK;
+  const int ho = (h + 2 - 3) / 2 + 1, wo = (wd + 2 - 3) / 2 + 1;
+  const long long total = (long long)n * ho * wo * (c / 8);
+  const long long blocks = (total + 255) / 256;
+  if (blocks > 0x7fffffffll) return cg::set_error(CG_EUNSUPPORTED, "cg_maxpool3x3s2: too large");
+  hipLaunchKernelGGL(maxpool3x3s2_kernel, dim3((unsigned)blocks), dim3(256), 0, (hipStream_t)hip_stream,
+                     (const uint16_t*)x, (uint16_t*)y, n, h, wd, c, ho, wo);
+  const hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return cg::set_error(CG_EHIP, "cg_maxpool3x3s2: %s", hipGetErrorString(e));
+  return CG_OK;
+}
+
+int cg_avgpool_fc(const void* x, const void* wfc, const float* bias, float* logits, int32_t n, int32_t hw, int32_t c,
+                  int32_t classes, void* hip_stream) {
+  if (!x || !wfc || !logits) return cg::set_error(CG_EINVAL, "cg_avgpool_fc: x, wfc and logits must not be NULL");
+  if (n < 0 || hw <= 0 || c <= 0 || classes <= 0) return cg::set_error(CG_EINVAL, "cg_avgpool_fc: bad size");
+  if ((size_t)c * sizeof(float) > 48 * 1024) return cg::set_error(CG_EUNSUPPORTED, "cg_avgpool_fc: at most 12288 channels");
+  if (n == 0) return CG_OK;
+  hipLaunchKernelGGL(avgpool_fc_kernel, dim3((unsigned)n), dim3(256), (size_t)c * sizeof(float), (hipStream_t)hip_stream,
+                     (const uint16_t*)x, (const uint16_t*)wfc, bias, logits, hw, c, classes);
+  const hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return cg::set_error(CG_EHIP, "cg_avgpool_fc: %s", hipGetErrorString(e));
+  return CG_OK;
+}
+
+}  // extern "C"

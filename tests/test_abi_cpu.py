@@ -139,3 +139,27 @@ def test_null_handle_paths():
     rc = B._lib.cg_conv_forward(None, 1, None, None, None, None, None, None, 0, None)
     assert rc == B.CG_EINVAL
     assert isinstance(B.cg_last_error(), str)
+
+
+def test_dense_ops_validate_without_a_gpu():
+    """cg_small_cin_conv / cg_maxpool3x3s2 / cg_avgpool_fc check their arguments before any HIP call."""
+    for call, code in (
+            (lambda: B.cg_small_cin_conv(0, 16, 0, 0, 16, 1, 8, 8, 3, 64, 7, 2, 3, True), B.CG_EINVAL),
+            (lambda: B.cg_small_cin_conv(16, 16, 0, 0, 16, 1, 8, 8, 5, 64, 3, 1, 1, True), B.CG_EUNSUPPORTED),
+            (lambda: B.cg_small_cin_conv(16, 16, 0, 0, 16, 1, 8, 8, 3, 48, 3, 1, 1, True), B.CG_EUNSUPPORTED),
+            (lambda: B.cg_small_cin_conv(16, 16, 0, 0, 16, 1, 8, 8, 3, 64, 4, 1, 1, True), B.CG_EUNSUPPORTED),
+            (lambda: B.cg_small_cin_conv(16, 16, 0, 0, 16, 1, 2, 2, 3, 64, 7, 2, 1, True), B.CG_EINVAL),
+            (lambda: B.cg_small_cin_conv(16, 16, 0, 0, 17, 1, 8, 8, 3, 64, 3, 1, 1, True), B.CG_EINVAL),
+            (lambda: B.cg_maxpool3x3s2(16, 0, 1, 8, 8, 8), B.CG_EINVAL),
+            (lambda: B.cg_maxpool3x3s2(16, 16, 1, 8, 8, 12), B.CG_EUNSUPPORTED),
+            (lambda: B.cg_maxpool3x3s2(16, 16, 1, 0, 8, 8), B.CG_EINVAL),
+            (lambda: B.cg_avgpool_fc(16, 0, 0, 16, 1, 4, 8, 2), B.CG_EINVAL),
+            (lambda: B.cg_avgpool_fc(16, 16, 0, 16, 1, 0, 8, 2), B.CG_EINVAL),
+            (lambda: B.cg_avgpool_fc(16, 16, 0, 16, 1, 4, 20000, 2), B.CG_EUNSUPPORTED)):
+        with pytest.raises(B.CGError) as e:
+            call()
+        assert e.value.code == code, B.cg_last_error()
+    # zero images: accepted, nothing to do
+    B.cg_small_cin_conv(16, 16, 0, 0, 16, 0, 8, 8, 3, 64, 7, 2, 3, True)
+    B.cg_maxpool3x3s2(16, 16, 0, 8, 8, 8)
+    B.cg_avgpool_fc(16, 16, 0, 16, 0, 4, 8, 2)

@@ -1,0 +1,104 @@
+"""GPU parity of the dense pieces of a ResNet around the gated layers (small-channel input
+convolution, 3x3 stride-2 max pooling, average pooling + fully connected layer, 1x1 stride-2
+shortcut convolution) against the CPU oracle, through the C ABI."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import cg_oracle as O
+from paper_1805_12549_amd import binding as B
+from paper_1805_12549_amd import workloads as W
+from tests import parity as P
+
+pytestmark = pytest.mark.gpu
+
+
+def _bf16(a):
+    return W.bf16_round(np.asarray(a, np.float32))
+
+
+def _dev(a, dtype=torch.bfloat16):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda().to(dtype).contiguous()
+
+
+def _stream():
+    return torch.cuda.current_stream().cuda_stream
+
+
+@pytest.mark.parametrize("n,h,w,c_in,c_out,k,stride,pad", [
+    (2, 224, 224, 3, 64, 7, 2, 3),        # the ImageNet input layer
+    (3, 37, 29, 3, 64, 7, 2, 3),          # ragged tiles
+    (2, 32, 32, 3, 128, 3, 1, 1),         # a CIFAR-style input layer, two channel blocks
+    (1, 9, 9, 4, 64, 5, 2, 2),
+    (2, 8, 8, 1, 64, 1, 1, 0),
+])
+def test_small_cin_conv(n, h, w, c_in, c_out, k, stride, pad):
+    rng = np.random.default_rng(n * 100 + h + k)
+    x = _bf16(rng.standard_normal((n, h, w, c_in)))
+    wt = _bf16(rng.standard_normal((c_out, k, k, c_in)) * np.sqrt(2.0 / (k * k * c_in)))
+    sc = rng.uniform(0.5, 1.5, c_out).astype(np.float32)
+    sh = (rng.standard_normal(c_out) * 0.1).astype(np.float32)
+    ho, wo = O.out_hw(h, w, k, k, stride, pad)
+    xd, wd_ = _dev(x), _dev(wt)
+    scd, shd = _dev(sc, torch.float32), _dev(sh, torch.float32)
+    for relu, with_affine in ((True, True), (False, False)):
+        y = torch.empty((n, ho, wo, c_out), dtype=torch.bfloat16, device="cuda")
+        B.cg_small_cin_conv(xd.data_ptr(), wd_.data_ptr(), scd.data_ptr() if with_affine else 0,
+                            shd.data_ptr() if with_affine else 0, y.data_ptr(), n, h, w, c_in, c_out, k, stride, pad,
+                            relu, _stream())
+        torch.cuda.synchronize()
+        ref = O.dense_conv(x, wt, stride=stride, pad=pad, scale=sc if with_affine else None,
+                           shift=sh if with_affine else None, relu=relu)
+        got = y.float().cpu().numpy().astype(np.float64)
+        tol = P.ATOL + P.RTOL * np.abs(ref) + P.bf16_ulp(ref)
+        assert (np.abs(got - ref) <= tol).all(), float(np.abs(got - ref).max())
+
+
+@pytest.mark.parametrize("n,h,w,c", [(2, 112, 112, 64), (3, 9, 7, 8), (1, 1, 1, 16), (2, 6, 5, 72)])
+def test_maxpool_bit_exact(n, h, w, c):
+    rng = np.random.default_rng(h * 10 + c)
+    x = _bf16(rng.standard_normal((n, h, w, c)) - 2.0)
+    xd = _dev(x)
+    y = torch.empty((n, (h - 1) // 2 + 1, (w - 1) // 2 + 1, c), dtype=torch.bfloat16, device="cuda")
+    B.cg_maxpool3x3s2(xd.data_ptr(), y.data_ptr(), n, h, w, c, _stream())
+    torch.cuda.synchronize()
+    assert np.array_equal(y.float().cpu().numpy().astype(np.float64), O.maxpool3x3s2(x))     # a maximum of bf16 values is exact
+
+
+@pytest.mark.parametrize("n,hw,c,classes", [(4, 49, 512, 1000), (2, 16, 64, 10), (1, 1, 24, 7)])
+def test_avgpool_fc(n, hw, c, classes):
+    rng = np.random.default_rng(hw + classes)
+    x = _bf16(np.maximum(rng.standard_normal((n, hw, c)), 0))
+    wfc = _bf16(rng.standard_normal((classes, c)) / np.sqrt(c))
+    b = rng.standard_normal(classes).astype(np.float32)
+    xd, wd_, bd = _dev(x), _dev(wfc), _dev(b, torch.float32)
+    out = torch.empty((n, classes), dtype=torch.float32, device="cuda")
+    B.cg_avgpool_fc(xd.data_ptr(), wd_.data_ptr(), bd.data_ptr(), out.data_ptr(), n, hw, c, classes, _stream())
+    B.cg_avgpool_fc(xd.data_ptr(), wd_.data_ptr(), 0, out.data_ptr(), 0, hw, c, classes, _stream())   # n = 0: nothing
+    torch.cuda.synchronize()
+    ref = O.avgpool_fc(x, wfc, b)
+    np.testing.assert_allclose(out.cpu().numpy(), ref, rtol=P.RTOL, atol=P.ATOL)
+
+
+@pytest.mark.parametrize("c_in,c_out,hw", [(64, 128, 56), (128, 256, 28), (256, 512, 14)])
+def test_shortcut_conv_1x1_stride2_dense(c_in, c_out, hw):
+    """The ResNet shortcut: a dense (c_base == c_in) 1x1 stride-2 layer of cg_conv_create, with scale/shift."""
+    shape = W.LayerShape("sc_%d" % c_in, 2, hw, hw, c_in, c_out, stride=2, pad=0, groups=1, k=1)
+    inp = W.make_inputs(shape, 600 + c_in, kind="iid", round_bf16=True)
+    rng = np.random.default_rng(c_in)
+    aff = dict(scale0=rng.uniform(0.5, 1.5, c_out), shift0=rng.normal(0, 0.1, c_out),
+               scale1=rng.uniform(0.5, 1.5, c_out), shift1=rng.normal(0, 0.1, c_out))
+    rep = P.run_float(inp, None, out_dtype=B.CG_BF16, epilogue=B.CG_EPI_AFFINE, affine=aff, name=shape.name)
+    assert rep.variant == B.CG_VARIANT_MFMA and rep.fired_frac == 0.0
+
+
+def test_dense_ops_reject_bad_arguments_before_any_launch():
+    with pytest.raises(B.CGError) as e:
+        B.cg_small_cin_conv(16, 16, 0, 0, 16, 1, 8, 8, 5, 64, 3, 1, 1, True)
+    assert e.value.code == B.CG_EUNSUPPORTED
+    with pytest.raises(B.CGError) as e:
+        B.cg_maxpool3x3s2(16, 16, 1, 8, 8, 12)
+    assert e.value.code == B.CG_EUNSUPPORTED
+    with pytest.raises(B.CGError) as e:
+        B.cg_avgpool_fc(0, 16, 0, 16, 1, 4, 8, 2)
+    assert e.value.code == B.CG_EINVAL
