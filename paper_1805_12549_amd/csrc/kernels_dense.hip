@@ -114,6 +114,98 @@ __global__ __launch_bounds__(256) void small_cin_conv_kernel(const uint16_t* __r
   }
 }
 
+// The same convolution for the ImageNet input layer's shape (7x7, stride 2, three input channels)
+// with everything unrolled: block = 16x16 output pixels x 64 channels; a thread owns four pixels
+// in a row x 16 channels, keeps the 13 x 3 input values a kernel row needs for them in registers
+// and reads each weight once for all four pixels (14 multiply-adds per LDS read instead of 3).
+__global__ __launch_bounds__(256) void conv7x7s2c3_kernel(const uint16_t* __restrict__ x, const uint16_t* __restrict__ w,
+                                                          const float* __restrict__ scale,
+                                                          const float* __restrict__ shift, uint16_t* __restrict__ y,
+                                                          int n, int h, int wd, int c_out, int pad, int ho, int wo,
+                                                          int relu) {
+  constexpr int K = 7, CI = 3, ST = 2, TILE = 16, TAPS = K * K * CI;
+  constexpr int PE = (TILE - 1) * ST + K;          // 37 patch rows / columns
+  constexpr int PROW = PE * CI + 1;                // floats per patch row (+1: rows of different bank phase)
+  extern __shared__ float lds[];
+  float* wl = lds;                                 // [TAPS][64]
+  float* xl = lds + TAPS * kCb;                    // [PE][PROW]
+  const int tid = threadIdx.x;
+  const int tiles_w = (wo + TILE - 1) / TILE, tiles_h = (ho + TILE - 1) / TILE;
+  int b = blockIdx.x;
+  const int tw = b % tiles_w;
+  b /= tiles_w;
+  const int th = b % tiles_h;
+  const int img = b / tiles_h;
+  const int cb = blockIdx.y;
+  for (int i = tid; i < TAPS * kCb; i += 256) {
+    const int co = i / TAPS, t = i - co * TAPS;
+    wl[t * kCb + co] = bf16_to_float(w[(long long)(cb * kCb + co) * TAPS + t]);
+  }
+  const int h0 = th * TILE * ST - pad, w0 = tw * TILE * ST - pad;
+  for (int i = tid; i < PE * PE * CI; i += 256) {
+    const int c = i % CI, q = i / CI;
+    const int pw = q % PE, ph = q / PE;
+    const int hi = h0 + ph, wi = w0 + pw;
+    float v = 0.0f;
+    if (hi >= 0 && hi < h && wi >= 0 && wi < wd) v = bf16_to_float(x[(((long long)img * h + hi) * wd + wi) * CI + c]);
+    xl[ph * PROW + pw * CI + c] = v;
+  }
+  __syncthreads();
+
+  const int quad = tid & 63, g = tid >> 6;         // a wavefront: one channel group, 64 pixel quads
+  const int oh = quad >> 2, oq = quad & 3;         // output row, quad (four columns) within the tile
+  float acc[4][16];
+#pragma unroll
+  for (int p = 0; p < 4; ++p)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) acc[p][i] = 0.0f;
+#pragma unroll 1
+  for (int r = 0; r < K; ++r) {
+    constexpr int NX = (3 * ST + K) * CI;          // 13 columns x 3 channels
+    float xr[NX];
+    const float* xrow = xl + (oh * ST + r) * PROW + (oq * 4 * ST) * CI;
+#pragma unroll
+    for (int i = 0; i < NX; ++i) xr[i] = xrow[i];
+    const float* wr = wl + (r * K * CI) * kCb + g * 16;
+#pragma unroll
+    for (int t = 0; t < K * CI; ++t) {
+      float wv[16];
+#pragma unroll
+      for (int q4 = 0; q4 < 4; ++q4) *(float4*)(wv + 4 * q4) = *(const float4*)(wr + t * kCb + 4 * q4);
+#pragma unroll
+      for (int p = 0; p < 4; ++p) {
+        const float xv = xr[p * ST * CI + t];      // tap (s, c) of pixel p: column 2p + s
+#pragma unroll
+        for (int i = 0; i < 16; ++i) acc[p][i] = fmaf(xv, wv[i], acc[p][i]);
+      }
+    }
+  }
+  const int oy = th * TILE + oh;
+  const int co0 = cb * kCb + g * 16;
+  float sc[16], sh[16];
+#pragma unroll
+  for (int i = 0; i < 16; ++i) {
+    sc[i] = scale ? scale[co0 + i] : 1.0f;
+    sh[i] = shift ? shift[co0 + i] : 0.0f;
+  }
+#pragma unroll
+  for (int p = 0; p < 4; ++p) {
+    const int ox = tw * TILE + oq * 4 + p;
+    if (oy < ho && ox < wo) {
+      uint16_t out[16];
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        float a = fmaf(acc[p][i], sc[i], sh[i]);
+        if (relu) a = fmaxf(a, 0.0f);
+        out[i] = float_to_bf16(a);
+      }
+      uint4* dst = (uint4*)(y + (((long long)img * ho + oy) * wo + ox) * c_out + co0);
+      dst[0] = *(const uint4*)(out);
+      dst[1] = *(const uint4*)(out + 8);
+    }
+  }
+}
+
 // 3x3 stride-2 max pooling with padding 1: the maximum over the taps inside the image.
 // One thread per (output pixel, 8 channels).
 __global__ __launch_bounds__(256) void maxpool3x3s2_kernel(const uint16_t* __restrict__ x, uint16_t* __restrict__ y, int n,
@@ -149,12 +241,14 @@ __global__ __launch_bounds__(256) void maxpool3x3s2_kernel(const uint16_t* __res
   *(uint4*)(y + (((long long)img * ho + oy) * wo + ox) * c + cc * 8) = *(const uint4*)out;
 }
 
-// Global average pooling over hw positions, then logits = W * mean + bias.  One block per image.
+// Global average pooling over hw positions, then logits = W * mean + bias.  One block per image and
+// 64 classes (every block averages its image again: the map is small and the blocks are many).
 __global__ __launch_bounds__(256) void avgpool_fc_kernel(const uint16_t* __restrict__ x, const uint16_t* __restrict__ wfc,
                                                          const float* __restrict__ bias, float* __restrict__ logits,
                                                          int hw, int c, int classes) {
   extern __shared__ float mean[];
   const int img = blockIdx.x;
+  const int k0 = blockIdx.y * 64, k1 = k0 + 64 < classes ? k0 + 64 : classes;
   const float inv = 1.0f / (float)hw;
   for (int ch = threadIdx.x; ch < c; ch += blockDim.x) {
     float s = 0.0f;
@@ -164,7 +258,7 @@ __global__ __launch_bounds__(256) void avgpool_fc_kernel(const uint16_t* __restr
   __syncthreads();
   // one wavefront per class: lanes stride over the channels, then a butterfly sum
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
-  for (int k = wave; k < classes; k += nw) {
+  for (int k = k0 + wave; k < k1; k += nw) {
     float s = 0.0f;
     for (int ch = lane; ch < c; ch += 64) s = fmaf(bf16_to_float(wfc[(long long)k * c + ch]), mean[ch], s);
 #pragma unroll
@@ -190,6 +284,17 @@ int cg_small_cin_conv(const void* x, const void* w, const float* scale, const fl
   if ((((uintptr_t)y) & 15) != 0) return cg::set_error(CG_EINVAL, "cg_small_cin_conv: y must be 16-byte aligned");
   if (n == 0) return CG_OK;
   const int ho = (h + 2 * pad - k) / stride + 1, wo = (wd + 2 * pad - k) / stride + 1;
+  if (k == 7 && stride == 2 && c_in == 3) {      // the ImageNet input layer: the unrolled kernel
+    const long long t16 = (long long)n * ((ho + 15) / 16) * ((wo + 15) / 16);
+    if (t16 > 0x7fffffffll) return cg::set_error(CG_EUNSUPPORTED, "cg_small_cin_conv: too many tiles");
+    const size_t lds16 = ((size_t)147 * kCb + (size_t)37 * (37 * 3 + 1)) * sizeof(float);
+    hipLaunchKernelGGL(conv7x7s2c3_kernel, dim3((unsigned)t16, (unsigned)(c_out / kCb)), dim3(256), lds16,
+                       (hipStream_t)hip_stream, (const uint16_t*)x, (const uint16_t*)w, scale, shift, (uint16_t*)y, n, h, wd,
+                       c_out, pad, ho, wo, relu);
+    const hipError_t e7 = hipGetLastError();
+    if (e7 != hipSuccess) return cg::set_error(CG_EHIP, "cg_small_cin_conv: %s", hipGetErrorString(e7));
+    return CG_OK;
+  }
   const long long tiles = (long long)n * ((ho + kTile - 1) / kTile) * ((wo + kTile - 1) / kTile);
   if (tiles > 0x7fffffffll) return cg::set_error(CG_EUNSUPPORTED, "cg_small_cin_conv: too many tiles");
   const int pe = (kTile - 1) * stride + k;
@@ -225,7 +330,8 @@ int cg_avgpool_fc(const void* x, const void* wfc, const float* bias, float* logi
   if (n < 0 || hw <= 0 || c <= 0 || classes <= 0) return cg::set_error(CG_EINVAL, "cg_avgpool_fc: bad size");
   if ((size_t)c * sizeof(float) > 48 * 1024) return cg::set_error(CG_EUNSUPPORTED, "cg_avgpool_fc: at most 12288 channels");
   if (n == 0) return CG_OK;
-  hipLaunchKernelGGL(avgpool_fc_kernel, dim3((unsigned)n), dim3(256), (size_t)c * sizeof(float), (hipStream_t)hip_stream,
+  hipLaunchKernelGGL(avgpool_fc_kernel, dim3((unsigned)n, (unsigned)((classes + 63) / 64)), dim3(256),
+                     (size_t)c * sizeof(float), (hipStream_t)hip_stream,
                      (const uint16_t*)x, (const uint16_t*)wfc, bias, logits, hw, c, classes);
   const hipError_t e = hipGetLastError();
   if (e != hipSuccess) return cg::set_error(CG_EHIP, "cg_avgpool_fc: %s", hipGetErrorString(e));

@@ -254,9 +254,23 @@ def main():
         for _ in range(3):
             net.forward(x)
         torch.cuda.synchronize()
+        # the forward pass only enqueues kernels on the current stream: capture it once, replay it
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            net.forward(x)
+            torch.cuda.synchronize()
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph, stream=side):
+                logits = net.forward(x)
+        torch.cuda.synchronize()
+        eager = net.forward(x)
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(eager, logits), "graph replay differs from the eager pass"
         t0 = time.perf_counter()
         for _ in range(args.steps):
-            net.forward(x)
+            graph.replay()
         torch.cuda.synchronize()
         dt = (time.perf_counter() - t0) / args.steps
         fired = None
