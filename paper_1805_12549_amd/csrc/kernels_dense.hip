@@ -114,96 +114,151 @@ __global__ __launch_bounds__(256) void small_cin_conv_kernel(const uint16_t* __r
   }
 }
 
-// The same convolution for the ImageNet input layer's shape (7x7, stride 2, three input channels)
-// with everything unrolled: block = 16x16 output pixels x 64 channels; a thread owns four pixels
-// in a row x 16 channels, keeps the 13 x 3 input values a kernel row needs for them in registers
-// and reads each weight once for all four pixels (14 multiply-adds per LDS read instead of 3).
-__global__ __launch_bounds__(256) void conv7x7s2c3_kernel(const uint16_t* __restrict__ x, const uint16_t* __restrict__ w,
-                                                          const float* __restrict__ scale,
-                                                          const float* __restrict__ shift, uint16_t* __restrict__ y,
-                                                          int n, int h, int wd, int c_out, int pad, int ho, int wo,
-                                                          int relu) {
+// The ImageNet input layer's shape (7x7, stride 2, three input channels) on the matrix cores.
+// Block = 16x16 output pixels x 64 channels, four wavefronts, each 64 pixels x 64 channels as 2x2
+// 32x32 MFMA blocks.  K is ordered kernel row by kernel row; within a row the 21 values (column,
+// channel) of a pixel are 21 contiguous bf16 of the input patch, padded to 24 = three 8-element
+// chunks (the three extra elements meet zero weights), so the pixel operand of a chunk is 16
+// contiguous bytes of the LDS patch, read as four words (the start is only 4-byte aligned).
+// 7 rows x 3 chunks = 21 chunks, padded to 22 = 11 K steps of 16.  The product is taken with the
+// weights as the row operand and their rows permuted (row rho holds channel
+// 16*((rho/4)%2) + 4*(rho/8) + rho%4), which leaves every lane with 16 consecutive channels of
+// one pixel per accumulator.
+typedef __attribute__((ext_vector_type(8))) __bf16 stem_bf16x8;
+typedef __attribute__((ext_vector_type(16))) float stem_f32x16;
+typedef __attribute__((ext_vector_type(4))) int stem_i32x4;
+
+__global__ __launch_bounds__(256) void conv7x7s2c3_mfma_kernel(const uint16_t* __restrict__ x,
+                                                               const uint16_t* __restrict__ w,
+                                                               const float* __restrict__ scale,
+                                                               const float* __restrict__ shift, uint16_t* __restrict__ y,
+                                                               int n, int h, int wd, int c_out, int pad, int ho, int wo,
+                                                               int relu, int tpb) {
   constexpr int K = 7, CI = 3, ST = 2, TILE = 16, TAPS = K * K * CI;
-  constexpr int PE = (TILE - 1) * ST + K;          // 37 patch rows / columns
-  constexpr int PROW = PE * CI + 1;                // floats per patch row (+1: rows of different bank phase)
-  extern __shared__ float lds[];
-  float* wl = lds;                                 // [TAPS][64]
-  float* xl = lds + TAPS * kCb;                    // [PE][PROW]
+  constexpr int PE = (TILE - 1) * ST + K;          // 37 patch rows / columns in use
+  constexpr int PR = 120;                          // bf16 per patch row (111 in use, the rest zero)
+  constexpr int PROWS = PE + 1;                    // one more zero row for the padding chunk
+  constexpr int NQ = 22;                           // 8-element K chunks
+  __shared__ __align__(16) uint16_t wl[NQ * kCb * 8];    // [chunk][row][8]
+  __shared__ __align__(16) uint16_t xl[PROWS * PR];
   const int tid = threadIdx.x;
+  // one block walks tpb tiles of a row: the weights are laid out once per block
   const int tiles_w = (wo + TILE - 1) / TILE, tiles_h = (ho + TILE - 1) / TILE;
+  const int strips = (tiles_w + tpb - 1) / tpb;
   int b = blockIdx.x;
-  const int tw = b % tiles_w;
-  b /= tiles_w;
+  const int tw0 = (b % strips) * tpb;
+  b /= strips;
   const int th = b % tiles_h;
   const int img = b / tiles_h;
   const int cb = blockIdx.y;
-  for (int i = tid; i < TAPS * kCb; i += 256) {
-    const int co = i / TAPS, t = i - co * TAPS;
-    wl[t * kCb + co] = bf16_to_float(w[(long long)(cb * kCb + co) * TAPS + t]);
+  const int tw1 = tw0 + tpb < tiles_w ? tw0 + tpb : tiles_w;
+
+  // weights: chunk q = (kernel row q/3, elements 8*(q%3) .. +8 of its 24), row = permuted channel.
+  // A thread lays out one (channel, kernel row): 21 contiguous weights become three chunks, the
+  // last three elements zero; the 22nd chunk of every row is zero.
+  if (tid < kCb) *(uint4*)(wl + (((NQ - 1) * kCb + tid) << 3)) = uint4{0u, 0u, 0u, 0u};
+  {
+    const uint16_t* wsrc = w + (long long)cb * kCb * TAPS;
+    for (int pr = tid; pr < kCb * K; pr += 256) {
+      const int col = pr / K, r = pr - col * K;
+      const uint16_t* src = wsrc + col * TAPS + r * (K * CI);
+      uint16_t v[24];
+#pragma unroll
+      for (int e = 0; e < K * CI; ++e) v[e] = src[e];
+      v[21] = v[22] = v[23] = 0;
+      const int ch = col & 31;
+      const int row = (col & 32) + 8 * ((ch & 15) >> 2) + 4 * (ch >> 4) + (ch & 3);   // inverse of the row permutation
+      uint16_t* dst = wl + (((3 * r) * kCb + row) << 3);
+      *(uint4*)(dst) = *(const uint4*)(v);
+      *(uint4*)(dst + kCb * 8) = *(const uint4*)(v + 8);
+      *(uint4*)(dst + 2 * kCb * 8) = *(const uint4*)(v + 16);
+    }
   }
+  const int lane = tid & 63, wave = tid >> 6;
+  const int lj = lane & 31, lh = lane >> 5;
+  // this lane's pixels: fragment 2*wave + fp covers tile rows 2*(2*wave+fp) and the next
+  int pbase[2];
+#pragma unroll
+  for (int fp = 0; fp < 2; ++fp) {
+    const int oh = 2 * (2 * wave + fp) + (lj >> 4), ow = lj & 15;
+    pbase[fp] = (oh * ST) * PR + ow * ST * CI;     // element offset of the pixel's window, kernel row 0
+  }
+  for (int tw = tw0; tw < tw1; ++tw) {
+  if (tw > tw0) __syncthreads();                   // the previous tile's patch has been read
+  // input patch as bf16, zero outside the image and in the padding
   const int h0 = th * TILE * ST - pad, w0 = tw * TILE * ST - pad;
-  for (int i = tid; i < PE * PE * CI; i += 256) {
-    const int c = i % CI, q = i / CI;
-    const int pw = q % PE, ph = q / PE;
+  // a thread fills one patch pixel (three channels) at a time; 40 pixel positions per row, the ones
+  // past the patch edge or outside the image are zero
+  constexpr int PPR = PR / CI;
+#pragma unroll
+  for (int u = 0; u < (PROWS * PPR + 255) / 256; ++u) {
+    const int pp = tid + 256 * u;
+    const int ph = pp / PPR, pw = pp - ph * PPR;
     const int hi = h0 + ph, wi = w0 + pw;
-    float v = 0.0f;
-    if (hi >= 0 && hi < h && wi >= 0 && wi < wd) v = bf16_to_float(x[(((long long)img * h + hi) * wd + wi) * CI + c]);
-    xl[ph * PROW + pw * CI + c] = v;
+    uint16_t v0 = 0, v1 = 0, v2 = 0;
+    if (pp < PROWS * PPR && ph < PE && pw < PE && hi >= 0 && hi < h && wi >= 0 && wi < wd) {
+      const uint16_t* src = x + (((long long)img * h + hi) * wd + wi) * CI;
+      v0 = src[0];
+      v1 = src[1];
+      v2 = src[2];
+    }
+    if (pp < PROWS * PPR) {
+      uint16_t* dst = xl + ph * PR + pw * CI;
+      dst[0] = v0;
+      dst[1] = v1;
+      dst[2] = v2;
+    }
   }
   __syncthreads();
 
-  const int quad = tid & 63, g = tid >> 6;         // a wavefront: one channel group, 64 pixel quads
-  const int oh = quad >> 2, oq = quad & 3;         // output row, quad (four columns) within the tile
-  float acc[4][16];
+  stem_f32x16 acc[2][2];
 #pragma unroll
-  for (int p = 0; p < 4; ++p)
+  for (int fp = 0; fp < 2; ++fp)
 #pragma unroll
-    for (int i = 0; i < 16; ++i) acc[p][i] = 0.0f;
-#pragma unroll 1
-  for (int r = 0; r < K; ++r) {
-    constexpr int NX = (3 * ST + K) * CI;          // 13 columns x 3 channels
-    float xr[NX];
-    const float* xrow = xl + (oh * ST + r) * PROW + (oq * 4 * ST) * CI;
+    for (int fc = 0; fc < 2; ++fc)
 #pragma unroll
-    for (int i = 0; i < NX; ++i) xr[i] = xrow[i];
-    const float* wr = wl + (r * K * CI) * kCb + g * 16;
+      for (int i = 0; i < 16; ++i) acc[fp][fc][i] = 0.0f;
 #pragma unroll
-    for (int t = 0; t < K * CI; ++t) {
-      float wv[16];
+  for (int st = 0; st < NQ / 2; ++st) {
+    const int q = 2 * st + lh;                     // this lane half's chunk of the K step
+    const int r = q / 3, j0 = (q % 3) * 8;
+    stem_i32x4 a[2], bq[2];
 #pragma unroll
-      for (int q4 = 0; q4 < 4; ++q4) *(float4*)(wv + 4 * q4) = *(const float4*)(wr + t * kCb + 4 * q4);
+    for (int fc = 0; fc < 2; ++fc) a[fc] = *(const stem_i32x4*)(wl + ((q * kCb + 32 * fc + lj) << 3));
 #pragma unroll
-      for (int p = 0; p < 4; ++p) {
-        const float xv = xr[p * ST * CI + t];      // tap (s, c) of pixel p: column 2p + s
-#pragma unroll
-        for (int i = 0; i < 16; ++i) acc[p][i] = fmaf(xv, wv[i], acc[p][i]);
-      }
+    for (int fp = 0; fp < 2; ++fp) {
+      const uint32_t* src = (const uint32_t*)(xl + pbase[fp] + r * PR + j0);
+      bq[fp] = stem_i32x4{(int)src[0], (int)src[1], (int)src[2], (int)src[3]};
     }
-  }
-  const int oy = th * TILE + oh;
-  const int co0 = cb * kCb + g * 16;
-  float sc[16], sh[16];
 #pragma unroll
-  for (int i = 0; i < 16; ++i) {
-    sc[i] = scale ? scale[co0 + i] : 1.0f;
-    sh[i] = shift ? shift[co0 + i] : 0.0f;
+    for (int fp = 0; fp < 2; ++fp)
+#pragma unroll
+      for (int fc = 0; fc < 2; ++fc)
+        acc[fp][fc] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(stem_bf16x8, a[fc]),
+                                                              __builtin_bit_cast(stem_bf16x8, bq[fp]), acc[fp][fc], 0, 0, 0);
   }
 #pragma unroll
-  for (int p = 0; p < 4; ++p) {
-    const int ox = tw * TILE + oq * 4 + p;
-    if (oy < ho && ox < wo) {
+  for (int fp = 0; fp < 2; ++fp) {
+    const int oy = th * TILE + 2 * (2 * wave + fp) + (lj >> 4), ox = tw * TILE + (lj & 15);
+    if (oy >= ho || ox >= wo) continue;
+#pragma unroll
+    for (int fc = 0; fc < 2; ++fc) {
+      const int co0 = cb * kCb + 32 * fc + 16 * lh;
       uint16_t out[16];
 #pragma unroll
       for (int i = 0; i < 16; ++i) {
-        float a = fmaf(acc[p][i], sc[i], sh[i]);
-        if (relu) a = fmaxf(a, 0.0f);
-        out[i] = float_to_bf16(a);
+        float v = acc[fp][fc][i];
+        if (scale) v *= scale[co0 + i];
+        if (shift) v += shift[co0 + i];
+        if (relu) v = fmaxf(v, 0.0f);
+        out[i] = float_to_bf16(v);
       }
       uint4* dst = (uint4*)(y + (((long long)img * ho + oy) * wo + ox) * c_out + co0);
       dst[0] = *(const uint4*)(out);
       dst[1] = *(const uint4*)(out + 8);
     }
   }
+  }   // tiles of the row
 }
 
 // 3x3 stride-2 max pooling with padding 1: the maximum over the taps inside the image.
@@ -284,13 +339,17 @@ int cg_small_cin_conv(const void* x, const void* w, const float* scale, const fl
   if ((((uintptr_t)y) & 15) != 0) return cg::set_error(CG_EINVAL, "cg_small_cin_conv: y must be 16-byte aligned");
   if (n == 0) return CG_OK;
   const int ho = (h + 2 * pad - k) / stride + 1, wo = (wd + 2 * pad - k) / stride + 1;
-  if (k == 7 && stride == 2 && c_in == 3) {      // the ImageNet input layer: the unrolled kernel
-    const long long t16 = (long long)n * ((ho + 15) / 16) * ((wo + 15) / 16);
+  if (k == 7 && stride == 2 && c_in == 3) {      // the ImageNet input layer: the matrix-core kernel
+    // 16x16 tiles per block, along a row: a whole row of tiles (the weight layout is then done once
+    // per row) when that still leaves two blocks per CU
+    const int tiles_w16 = (wo + 15) / 16;
+    const long long rows16 = (long long)n * ((ho + 15) / 16) * (c_out / kCb);
+    const int tpb = rows16 >= 512 ? tiles_w16 : 1;
+    const long long t16 = (long long)n * ((ho + 15) / 16) * ((tiles_w16 + tpb - 1) / tpb);
     if (t16 > 0x7fffffffll) return cg::set_error(CG_EUNSUPPORTED, "cg_small_cin_conv: too many tiles");
-    const size_t lds16 = ((size_t)147 * kCb + (size_t)37 * (37 * 3 + 1)) * sizeof(float);
-    hipLaunchKernelGGL(conv7x7s2c3_kernel, dim3((unsigned)t16, (unsigned)(c_out / kCb)), dim3(256), lds16,
+    hipLaunchKernelGGL(conv7x7s2c3_mfma_kernel, dim3((unsigned)t16, (unsigned)(c_out / kCb)), dim3(256), 0,
                        (hipStream_t)hip_stream, (const uint16_t*)x, (const uint16_t*)w, scale, shift, (uint16_t*)y, n, h, wd,
-                       c_out, pad, ho, wo, relu);
+                       c_out, pad, ho, wo, relu, tpb);
     const hipError_t e7 = hipGetLastError();
     if (e7 != hipSuccess) return cg::set_error(CG_EHIP, "cg_small_cin_conv: %s", hipGetErrorString(e7));
     return CG_OK;
