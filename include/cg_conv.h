@@ -181,7 +181,7 @@ const char* cg_last_error(void);
 
 /* Convolution on few input channels (the 7x7 stride-2 input layer): c_in in [1,4], c_out a multiple of
  * 64, k odd <= 7, stride 1|2, zero padding pad < k.  y[n][ho][wo][c_out] = relu?(scale*conv + shift);
- * scale / shift: [c_out] floats, nullable (= 1 / 0).  y 16-byte aligned. */
+ * scale / shift: [c_out] floats, nullable (= 1 / 0).  y, scale, shift 16-byte aligned. */
 int cg_small_cin_conv(const void* x, const void* w, const float* scale, const float* shift, void* y, int32_t n,
                       int32_t h, int32_t wd, int32_t c_in, int32_t c_out, int32_t k, int32_t stride, int32_t pad,
                       int32_t relu, void* hip_stream);

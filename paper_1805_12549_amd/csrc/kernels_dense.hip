@@ -244,12 +244,18 @@ __global__ __launch_bounds__(256) void conv7x7s2c3_mfma_kernel(const uint16_t* _
 #pragma unroll
     for (int fc = 0; fc < 2; ++fc) {
       const int co0 = cb * kCb + 32 * fc + 16 * lh;
+      float sc[16], sh[16];
+#pragma unroll
+      for (int q4 = 0; q4 < 4; ++q4) {
+        const float4 a4 = scale ? *(const float4*)(scale + co0 + 4 * q4) : float4{1.0f, 1.0f, 1.0f, 1.0f};
+        const float4 b4 = shift ? *(const float4*)(shift + co0 + 4 * q4) : float4{0.0f, 0.0f, 0.0f, 0.0f};
+        sc[4 * q4] = a4.x, sc[4 * q4 + 1] = a4.y, sc[4 * q4 + 2] = a4.z, sc[4 * q4 + 3] = a4.w;
+        sh[4 * q4] = b4.x, sh[4 * q4 + 1] = b4.y, sh[4 * q4 + 2] = b4.z, sh[4 * q4 + 3] = b4.w;
+      }
       uint16_t out[16];
 #pragma unroll
       for (int i = 0; i < 16; ++i) {
-        float v = acc[fp][fc][i];
-        if (scale) v *= scale[co0 + i];
-        if (shift) v += shift[co0 + i];
+        float v = acc[fp][fc][i] * sc[i] + sh[i];
         if (relu) v = fmaxf(v, 0.0f);
         out[i] = float_to_bf16(v);
       }
@@ -336,7 +342,8 @@ int cg_small_cin_conv(const void* x, const void* w, const float* scale, const fl
   if (k < 1 || k > 7 || !(k & 1)) return cg::set_error(CG_EUNSUPPORTED, "cg_small_cin_conv: kernel size must be odd, at most 7");
   if (stride < 1 || stride > 2 || pad < 0 || pad >= k) return cg::set_error(CG_EINVAL, "cg_small_cin_conv: bad stride or pad");
   if (h + 2 * pad < k || wd + 2 * pad < k) return cg::set_error(CG_EINVAL, "cg_small_cin_conv: kernel larger than the padded input");
-  if ((((uintptr_t)y) & 15) != 0) return cg::set_error(CG_EINVAL, "cg_small_cin_conv: y must be 16-byte aligned");
+  if ((((uintptr_t)y) | ((uintptr_t)scale) | ((uintptr_t)shift)) & 15)
+    return cg::set_error(CG_EINVAL, "cg_small_cin_conv: y, scale and shift must be 16-byte aligned");
   if (n == 0) return CG_OK;
   const int ho = (h + 2 * pad - k) / stride + 1, wo = (wd + 2 * pad - k) / stride + 1;
   if (k == 7 && stride == 2 && c_in == 3) {      // the ImageNet input layer: the matrix-core kernel
