@@ -302,19 +302,39 @@ __global__ __launch_bounds__(256) void maxpool3x3s2_kernel(const uint16_t* __res
   *(uint4*)(y + (((long long)img * ho + oy) * wo + ox) * c + cc * 8) = *(const uint4*)out;
 }
 
-// Global average pooling over hw positions, then logits = W * mean + bias.  One block per image and
-// 64 classes (every block averages its image again: the map is small and the blocks are many).
-__global__ __launch_bounds__(256) void avgpool_fc_kernel(const uint16_t* __restrict__ x, const uint16_t* __restrict__ wfc,
+// Global average pooling over hw positions, then logits = W * mean + bias.  One block of sixteen
+// wavefronts per image and 256 classes: the map is averaged by all threads (positions split over
+// thread groups, partial sums met in LDS), then every wavefront takes a share of the classes.
+__global__ __launch_bounds__(1024) void avgpool_fc_kernel(const uint16_t* __restrict__ x, const uint16_t* __restrict__ wfc,
                                                          const float* __restrict__ bias, float* __restrict__ logits,
                                                          int hw, int c, int classes) {
   extern __shared__ float mean[];
   const int img = blockIdx.x;
-  const int k0 = blockIdx.y * 64, k1 = k0 + 64 < classes ? k0 + 64 : classes;
+  const int k0 = blockIdx.y * 256, k1 = k0 + 256 < classes ? k0 + 256 : classes;
   const float inv = 1.0f / (float)hw;
-  for (int ch = threadIdx.x; ch < c; ch += blockDim.x) {
-    float s = 0.0f;
-    for (int p = 0; p < hw; ++p) s += bf16_to_float(x[((long long)img * hw + p) * c + ch]);
-    mean[ch] = s * inv;
+  {
+    // thread group g of (blockDim / cpad) takes positions g, g + groups, ...; cpad = channels rounded
+    // up to 64; the groups' partial sums sit behind the means in LDS and are added in a fixed order
+    float* part = mean + c;                        // [groups][cpad], at most blockDim floats
+    const int cpad = (c + 63) & ~63;
+    const int groups = (int)blockDim.x / cpad > 0 ? (int)blockDim.x / cpad : 1;
+    for (int ch0 = 0; ch0 < c; ch0 += groups > 1 ? c : (int)blockDim.x) {
+      const int ch = ch0 + (int)threadIdx.x % cpad, g = (int)threadIdx.x / cpad;
+      float s = 0.0f;
+      if (ch < c && g < groups)
+        for (int p = g; p < hw; p += groups) s += bf16_to_float(x[((long long)img * hw + p) * c + ch]);
+      if (groups == 1) {
+        if (ch < c) mean[ch] = s * inv;
+      } else {
+        if (g < groups) part[g * cpad + (int)threadIdx.x % cpad] = s;
+        __syncthreads();
+        if ((int)threadIdx.x < c) {
+          float t = 0.0f;
+          for (int gg = 0; gg < groups; ++gg) t += part[gg * cpad + threadIdx.x];
+          mean[threadIdx.x] = t * inv;
+        }
+      }
+    }
   }
   __syncthreads();
   // one wavefront per class: lanes stride over the channels, then a butterfly sum
@@ -394,10 +414,10 @@ int cg_avgpool_fc(const void* x, const void* wfc, const float* bias, float* logi
                   int32_t classes, void* hip_stream) {
   if (!x || !wfc || !logits) return cg::set_error(CG_EINVAL, "cg_avgpool_fc: x, wfc and logits must not be NULL");
   if (n < 0 || hw <= 0 || c <= 0 || classes <= 0) return cg::set_error(CG_EINVAL, "cg_avgpool_fc: bad size");
-  if ((size_t)c * sizeof(float) > 48 * 1024) return cg::set_error(CG_EUNSUPPORTED, "cg_avgpool_fc: at most 12288 channels");
+  if (c > 11264) return cg::set_error(CG_EUNSUPPORTED, "cg_avgpool_fc: at most 11264 channels");
   if (n == 0) return CG_OK;
-  hipLaunchKernelGGL(avgpool_fc_kernel, dim3((unsigned)n, (unsigned)((classes + 63) / 64)), dim3(256),
-                     (size_t)c * sizeof(float), (hipStream_t)hip_stream,
+  hipLaunchKernelGGL(avgpool_fc_kernel, dim3((unsigned)n, (unsigned)((classes + 255) / 256)), dim3(1024),
+                     ((size_t)c + 1024) * sizeof(float), (hipStream_t)hip_stream,
                      (const uint16_t*)x, (const uint16_t*)wfc, bias, logits, hw, c, classes);
   const hipError_t e = hipGetLastError();
   if (e != hipSuccess) return cg::set_error(CG_EHIP, "cg_avgpool_fc: %s", hipGetErrorString(e));
