@@ -26,6 +26,7 @@ if str(ROOT) not in sys.path:
     sys.path.insert(0, str(ROOT))
 
 PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA, published
+PEAK_INT8_TOPS = 5000.0       # MI355X dense int8 MFMA, published
 PEAK_HBM_GBS = 8000.0
 
 
@@ -42,6 +43,8 @@ def parse():
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying a HIP graph")
     ap.add_argument("--variant", default="auto", choices=["auto", "blockskip", "compact", "rows"],
                     help="kernel family (auto = what the library picks)")
+    ap.add_argument("--dtype", default="bf16", choices=["bf16", "int8"],
+                    help="bf16 (the headline workload) or int8 (int8 activations/weights, int32 sums, int8 requantised output)")
     ap.add_argument("--grouped", action="store_true",
                     help="channel grouping (output group i takes input group i as its base path) instead of the "
                          "default fixed base channels")
@@ -77,25 +80,41 @@ def main():
     layers = []
     t_gen = time.perf_counter()
     for li, s in enumerate(shapes):
-        inp = W.make_inputs(s, W.seed_for(3, li), kind=args.kind, rho=args.rho, round_bf16=True,
+        i8 = args.dtype == "int8"
+        eb = 1 if i8 else 2
+        tdt = torch.int8 if i8 else torch.bfloat16
+        inp = W.make_inputs(s, W.seed_for(4 if i8 else 3, li), kind=args.kind, rho=args.rho, round_bf16=not i8,
                             grouped=args.grouped)
-        gate = W.calibrate_gate(inp, args.rho, sample_images=8)
-        x_bytes = s.n * s.h * s.w * s.c_in * 2
-        y_bytes = s.m * s.c_out * 2
+        if i8:
+            inp_f = inp
+            inp = W.quantize_int8(inp_f)
+            gate = W.calibrate_gate_int8(inp, args.rho, sample_images=8)
+            rq = W.requant_params(inp, np.random.default_rng(li))
+        else:
+            gate = W.calibrate_gate(inp, args.rho, sample_images=8)
+        x_bytes = s.n * s.h * s.w * s.c_in * eb
+        y_bytes = s.m * s.c_out * eb
         nset = max(2, int(np.ceil(600e6 / (x_bytes + y_bytes))))      # rotate past the 256 MB infinity cache
-        x0 = torch.from_numpy(inp.x).to(dev).to(torch.bfloat16)
+        x0 = torch.from_numpy(inp.x).to(dev).to(tdt)
         xs = [x0] + [x0.clone() for _ in range(nset - 1)]
-        ys = [torch.empty((s.n, s.ho, s.wo, s.c_out), dtype=torch.bfloat16, device=dev) for _ in range(nset)]
+        ys = [torch.empty((s.n, s.ho, s.wo, s.c_out), dtype=tdt, device=dev) for _ in range(nset)]
         bms = [torch.empty((s.m, s.c_out // 32), dtype=torch.int32, device=dev) for _ in range(nset)]
-        wb = torch.from_numpy(inp.w_base).to(dev).to(torch.bfloat16)
-        wc = torch.from_numpy(inp.w_cond).to(dev).to(torch.bfloat16)
+        wb = torch.from_numpy(inp.w_base).to(dev).to(tdt)
+        wc = torch.from_numpy(inp.w_cond).to(dev).to(tdt)
         wfull = torch.cat([wb, wc], dim=-1).contiguous()
-        common = dict(n_max=s.n, h=s.h, w=s.w, c_in=s.c_in, c_out=s.c_out, in_dtype=B.CG_BF16, out_dtype=B.CG_BF16,
-                      stride=s.stride, pad=s.pad, epilogue=B.CG_EPI_RELU, variant=variant)
-        gated = B.GatedConv(c_base=s.c_base, w_base=wb, w_cond=wc, gate_mean=gate.mean, gate_var=gate.var,
-                            delta=gate.delta, groups=s.groups if args.grouped else 0, tau_c=args.tau_c, **common)
+        common = dict(n_max=s.n, h=s.h, w=s.w, c_in=s.c_in, c_out=s.c_out, in_dtype=B.CG_I8 if i8 else B.CG_BF16,
+                      out_dtype=B.CG_I8 if i8 else B.CG_BF16, stride=s.stride, pad=s.pad, epilogue=B.CG_EPI_RELU,
+                      variant=variant)
+        if i8:
+            common.update(rq)
+            gkw = dict(gate_thr_i32=gate)
+        else:
+            gkw = dict(gate_mean=gate.mean, gate_var=gate.var, delta=gate.delta)
+        gated = B.GatedConv(c_base=s.c_base, w_base=wb, w_cond=wc, groups=s.groups if args.grouped else 0,
+                            tau_c=args.tau_c, **gkw, **common)
         dense = None if args.no_dense else B.GatedConv(c_base=s.c_in, w_base=wfull, w_cond=None, **common)
-        layers.append(dict(shape=s, inp=inp, gate=gate, xs=xs, ys=ys, bms=bms, gated=gated, dense=dense, nset=nset))
+        layers.append(dict(shape=s, inp=inp, gate=gate, xs=xs, ys=ys, bms=bms, gated=gated, dense=dense, nset=nset,
+                           rq=rq if i8 else None))
     torch.cuda.synchronize()
     t_gen = time.perf_counter() - t_gen
 
@@ -194,22 +213,26 @@ def main():
         s = L["shape"]
         kp, kr = 9 * s.c_base, 9 * (s.c_in - s.c_base)
         alg_flops += 2.0 * s.m * s.c_out * (kp + L["rho"] * kr)
-        alg_bytes += s.n * s.h * s.w * s.c_in * 2 + s.m * s.c_out * 2 + s.c_out * 9 * s.c_in * 2 + s.m * s.c_out / 8
+        ebl = 1 if args.dtype == "int8" else 2
+        alg_bytes += (s.n * s.h * s.w * s.c_in + s.m * s.c_out + s.c_out * 9 * s.c_in) * ebl + s.m * s.c_out / 8
     t_kernel_us = sum(L["us_gated"] for L in layers)
     achieved = alg_flops / (t_kernel_us * 1e-6) / 1e12
     traffic = None     # measured HBM bytes per launch, from the committed counter summary
     tfile = ROOT / "profiles" / "hbm_traffic_gated_conv_rows_kernel_imagenet_resnet18_bf16_n64.txt"
+    peak = PEAK_INT8_TOPS if args.dtype == "int8" else PEAK_BF16_TFLOPS
     if (tfile.exists() and args.batch == 64 and not args.layers and args.kind == "coherent" and not args.grouped
+            and args.dtype == "bf16"
             and args.tau_c == 0.0
             and layers[0]["gated"].variant == B.CG_VARIANT_MFMA_ROWS):
         m = re.search(r"^bytes_per_launch:\s*(\d+)", tfile.read_text(), re.M)
         traffic = int(m.group(1)) if m else None
-    roofline = dict(bound="mfma", achieved=round(achieved, 2), peak=PEAK_BF16_TFLOPS, unit="TFLOP/s",
-                    frac=round(achieved / PEAK_BF16_TFLOPS, 4), traffic=traffic,
-                    kernel={B.CG_VARIANT_MFMA: "gated_conv_mfma_kernel<bf16>",
-                            B.CG_VARIANT_MFMA_COMPACT: "gated_conv_compact_kernel<bf16>",
-                            B.CG_VARIANT_MFMA_ROWS: "gated_conv_rows_kernel<bf16>"}.get(
-                                layers[0]["gated"].variant, "naive_kernel"), avg_launch_us=round(t_kernel_us / len(layers), 2),
+    roofline = dict(bound="mfma", achieved=round(achieved, 2), peak=peak,
+                    unit="TOP/s" if args.dtype == "int8" else "TFLOP/s",
+                    frac=round(achieved / peak, 4), traffic=traffic,
+                    kernel={B.CG_VARIANT_MFMA: "gated_conv_mfma_kernel",
+                            B.CG_VARIANT_MFMA_COMPACT: "gated_conv_compact_kernel",
+                            B.CG_VARIANT_MFMA_ROWS: "gated_conv_rows_kernel"}.get(
+                                layers[-1]["gated"].variant, "naive_kernel") + "<%s>" % args.dtype, avg_launch_us=round(t_kernel_us / len(layers), 2),
                     algorithmic_gflop_per_launch=round(alg_flops / len(layers) / 1e9, 3),
                     hbm_gbs_algorithmic=round(alg_bytes / (t_kernel_us * 1e-6) / 1e9, 1),
                     hbm_frac=round(alg_bytes / (t_kernel_us * 1e-6) / 1e9 / PEAK_HBM_GBS, 4))
@@ -222,6 +245,14 @@ def main():
         ops_cpu = 0
         for L in layers:
             s, inp, gate = L["shape"], L["inp"], L["gate"]
+            if args.dtype == "int8":
+                tc = time.perf_counter()
+                O.forward_int8(inp.x, inp.w_base, inp.w_cond, gate, stride=s.stride, pad=s.pad, out_i8=True,
+                               epilogue=O.RELU, want_partials=False, groups=s.groups if args.grouped else 1,
+                               tau_c=float(np.float32(args.tau_c)), **L["rq"])
+                t_cpu += time.perf_counter() - tc
+                ops_cpu += 2 * s.dense_macs
+                continue
             x64 = inp.x.astype(np.float64)
             wb64, wc64 = inp.w_base.astype(np.float64), inp.w_cond.astype(np.float64)
             tc = time.perf_counter()
@@ -233,8 +264,8 @@ def main():
         cores = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
         cpu = dict(value=round(ops_cpu / t_cpu / 1e12, 5), unit="TOP/s", cores=cores, kind="oracle",
                    seconds=round(t_cpu, 2),
-                   sample="one pass of the full workload (all layers, batch %d), fp64, both branches evaluated"
-                          % args.batch)
+                   sample="one pass of the full workload (all layers, batch %d), %s, both branches evaluated"
+                          % (args.batch, "int32 sums" if args.dtype == "int8" else "fp64"))
 
     per_layer = []
     for L in layers:
@@ -252,10 +283,10 @@ def main():
                   "per-layer us beside the dense MFMA conv in config.per_layer",
         "value": round(value, 2), "unit": "TOP/s", "n_gpus": 1, "steps": steps, "warmup": warm,
         "ms_per_step": round(ms_per_step, 5), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": "ImageNet-shaped ResNet-18 gated 3x3 convs (configs[2]): batch %d, bf16 NHWC, G=4, "
+        "dtype": args.dtype, "data": "synthetic",
+        "config": {"workload": "ImageNet-shaped ResNet-18 gated 3x3 convs (configs[2]): batch %d, %s NHWC, G=4, "
                                "%s gate maps, target firing %.2f%s; step = all %d layers" %
-                               (args.batch, args.kind, args.rho,
+                               (args.batch, args.dtype, args.kind, args.rho,
                                 (", channel grouping" if args.grouped else "") +
                                 (", channel-wise gate tau_c=%.2f" % args.tau_c if args.tau_c > 0 else ""), len(layers)),
                    "launch": "hip graph replay" if graph is not None else "eager",
