@@ -342,7 +342,7 @@ __global__ __launch_bounds__(NWV * 64, 2) void gated_conv_rows_kernel(
   if (g.grp_mode == 1) {
     base_ch0 = gap_start = (cbk * kBn / p.cpg) * p.c_base;
   } else if (g.grp_mode == 2) {
-    base_ch0 = cbk * g.gsp * p.c_base;
+    base_ch0 = p.groups > 1 ? cbk * g.gsp * p.c_base : 0;   // (without grouping: a base group padded with zero weights)
     gap_len = 0;
   }
   auto x_src = [&](int sg) __attribute__((always_inline)) {
@@ -922,6 +922,17 @@ Mfma3Plan mfma3_plan(const cg_conv_desc& d) {
     } else {
       return g;
     }
+  }
+  if (d.groups <= 1 && base_k % (2 * g.ch) != 0 && base_k % g.ch == 0 && base_k < d.c_in &&
+      d.c_in % (2 * g.ch) == 0) {
+    // A base group of one 16-byte chunk (16 int8 channels) is below the two-chunk K granule: the base
+    // phase then walks two chunks with zero weights on the second, and the conditional phase all
+    // input channels with zero weights on the base ones - the packing of a block that covers
+    // several groups, with one group.
+    g.grp_mode = 2;
+    g.gsp = 2;
+    base_k = 2 * d.c_base;
+    c_cond = d.c_in;
   }
   if (base_k % (4 * g.ch) == 0 && c_cond % (4 * g.ch) == 0)
     g.cps = 4;

@@ -22,9 +22,11 @@ VNAMES = ["blockskip", "compact", "rows"]
 def _supported(shape, variant, int8=False):
     if variant == B.CG_VARIANT_MFMA_COMPACT:
         return shape.k == 3
-    if variant == B.CG_VARIANT_MFMA_ROWS:      # 3x3, K stages of two 16-byte channel chunks
+    if variant == B.CG_VARIANT_MFMA_ROWS:      # 3x3, K stages of two 16-byte channel chunks (a one-chunk base group is padded)
         two_chunks = 32 if int8 else 16
-        return shape.k == 3 and shape.c_base % two_chunks == 0 and (shape.c_in - shape.c_base) % two_chunks == 0
+        whole = shape.c_base % two_chunks == 0 and (shape.c_in - shape.c_base) % two_chunks == 0
+        padded = shape.c_base % (two_chunks // 2) == 0 and shape.c_in % two_chunks == 0 and shape.c_base < shape.c_in
+        return shape.k == 3 and (whole or padded)
     return True
 
 
