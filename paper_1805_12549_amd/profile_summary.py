@@ -85,8 +85,35 @@ def traffic(fetch_csv: str, write_csv: str, copy_bytes: int = 256 << 20, kernel:
     return "\n".join(out) + "\n"
 
 
+def mfma_busy(counter_csv: str, trace_us, kernel: str = "gated_conv") -> str:
+    """Executed matrix-core work per launch of the layer kernel from SQ_VALU_MFMA_BUSY_CYCLES (summed over
+    the SIMDs; a 32x32x16 bf16 MFMA keeps its SIMD busy 32 cycles for 32768 flops, i.e. 1024 flops per busy
+    cycle) and the utilisation against the 2.5 PFLOP/s peak for the given per-layer times (microseconds)."""
+    import csv
+    vals = [float(r["Counter_Value"]) for r in csv.DictReader(open(counter_csv))
+            if r["Counter_Name"] == "SQ_VALU_MFMA_BUSY_CYCLES" and kernel in r["Kernel_Name"]]
+    out = ["source: rocprofv3 --pmc SQ_VALU_MFMA_BUSY_CYCLES on paper_1805_12549_amd.traffic_probe; times: bench.py per_layer us_gated",
+           "%-8s %-18s %-16s %-10s %-12s" % ("launch", "mfma_busy_cycles", "executed_gflop", "us_gated", "mfma_util")]
+    for i, v in enumerate(vals):
+        gflop = v * 1024 / 1e9
+        t = trace_us[i] if i < len(trace_us) else float("nan")
+        out.append("%-8d %-18.0f %-16.2f %-10.2f %-12.3f" % (i, v, gflop, t, gflop * 1e9 / (t * 1e-6) / 2.5e15))
+    if vals and len(trace_us) >= len(vals):
+        tot = sum(vals) * 1024
+        out.append("all launches: executed %.1f GFLOP in %.1f us -> %.3f of the bf16 MFMA peak" % (
+            tot / 1e9, sum(trace_us[:len(vals)]), tot / (sum(trace_us[:len(vals)]) * 1e-6) / 2.5e15))
+    out += ["commands (after cd /tmp && export TMPDIR=/tmp, from the repository root):",
+            "  rocprofv3 --pmc SQ_VALU_MFMA_BUSY_CYCLES SQ_BUSY_CYCLES GRBM_GUI_ACTIVE --output-format csv -d gpurun_out/prof_mfma -o r "
+            "-- python3 -m paper_1805_12549_amd.traffic_probe",
+            "  python -m paper_1805_12549_amd.profile_summary --mfma gpurun_out/prof_mfma/r_counter_collection.csv <us_gated of the 7 layers>",
+            "launches 0..6 = the 7 ImageNet-shaped ResNet-18 gated 3x3 layers, batch 64, bf16, one cold-cache forward each"]
+    return "\n".join(out) + "\n"
+
+
 if __name__ == "__main__":
-    if sys.argv[1] == "--traffic":
+    if sys.argv[1] == "--mfma":
+        sys.stdout.write(mfma_busy(sys.argv[2], [float(v) for v in sys.argv[3:]]))
+    elif sys.argv[1] == "--traffic":
         sys.stdout.write(traffic(sys.argv[2], sys.argv[3]))
     else:
         sys.stdout.write(summarize(sys.argv[1], sys.argv[2] if len(sys.argv) > 2 else ""))
