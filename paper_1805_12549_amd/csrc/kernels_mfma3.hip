@@ -996,6 +996,26 @@ Mfma3Plan mfma3_plan(const cg_conv_desc& d) {
       int t = tr;
       while (t >= 1 && (long long)patch_rows(t) * P * sb > c.pkb * 1024) --t;
       if (t < 1 || 4 * t < 3 * tr) continue;
+      {
+        // Balance the grid: with fewer rows per tile the tiles may come out as a whole number of
+        // rounds over the CUs (256 CUs, two workgroups each where LDS allows), which shortens the
+        // longest CU's share.  Cost of a choice = rounds x (rows per tile + a per-round share for
+        // prologue, gate and epilogue); ties keep the larger tile.
+        const int gkb = 3 * g.cps;
+        const long long slots = 256ll * ((2 * c.pkb + 2 * gkb + 6 <= 80) ? 2 : 1);
+        const int tmax = t;
+        double best = 1e30;
+        for (int tt = tmax; 4 * tt >= 3 * tr && tt >= 1; --tt) {     // (three quarters of the pixel slots stay in use)
+          const long long wg = ((rows + tt - 1) / tt) * g.n_cb;
+          if (nf == 2 && wg < 256) continue;
+          const long long rounds = (wg + slots - 1) / slots;
+          const double cost = (double)rounds * (tt + 0.35 * tmax);
+          if (cost < best - 1e-9) {
+            best = cost;
+            t = tt;
+          }
+        }
+      }
       const long long tiles = (rows + t - 1) / t;
       if (tiles * g.n_cb < c.min_wg) continue;
       if (nf == 2 && tiles * g.n_cb < 256) continue;   // the large tile only when it still fills the CUs
