@@ -996,6 +996,7 @@ Mfma3Plan mfma3_plan(const cg_conv_desc& d) {
       int t = tr;
       while (t >= 1 && (long long)patch_rows(t) * P * sb > c.pkb * 1024) --t;
       if (t < 1 || 4 * t < 3 * tr) continue;
+      if (nf == 2 && ((rows + t - 1) / t) * g.n_cb < 256) continue;   // the large tile only when it still fills the CUs
       {
         // Balance the grid: with fewer rows per tile the tiles may come out as a whole number of
         // rounds over the CUs (256 CUs, two workgroups each where LDS allows), which shortens the
@@ -1007,7 +1008,6 @@ Mfma3Plan mfma3_plan(const cg_conv_desc& d) {
         double best = 1e30;
         for (int tt = tmax; 4 * tt >= 3 * tr && tt >= 1; --tt) {     // (three quarters of the pixel slots stay in use)
           const long long wg = ((rows + tt - 1) / tt) * g.n_cb;
-          if (nf == 2 && wg < 256) continue;
           const long long rounds = (wg + slots - 1) / slots;
           const double cost = (double)rounds * (tt + 0.35 * tmax);
           if (cost < best - 1e-9) {
@@ -1018,7 +1018,6 @@ Mfma3Plan mfma3_plan(const cg_conv_desc& d) {
       }
       const long long tiles = (rows + t - 1) / t;
       if (tiles * g.n_cb < c.min_wg) continue;
-      if (nf == 2 && tiles * g.n_cb < 256) continue;   // the large tile only when it still fills the CUs
       g.nwv = c.nwv;
       g.nf = nf;
       g.nc = 2;
