@@ -175,8 +175,7 @@ const char* cg_last_error(void);
  * ResNet-18): none of them is gated.  bf16 activations and weights (NHWC / [c_out][k][k][c_in]),
  * fp32 accumulation, all pointers DEVICE, nothing allocated, work only enqueued on hip_stream.
  * Each returns CG_OK or an error code with text in cg_last_error(); arguments are checked before
- * any HIP call.  (A 1x1 stride-2 shortcut convolution is a dense layer of cg_conv_create:
- * kh = kw = 1, c_base == c_in.)
+ * any HIP call.
  */
 
 /* Convolution on few input channels (the 7x7 stride-2 input layer): c_in in [1,4], c_out a multiple of
@@ -185,6 +184,13 @@ const char* cg_last_error(void);
 int cg_small_cin_conv(const void* x, const void* w, const float* scale, const float* shift, void* y, int32_t n,
                       int32_t h, int32_t wd, int32_t c_in, int32_t c_out, int32_t k, int32_t stride, int32_t pad,
                       int32_t relu, void* hip_stream);
+
+/* 1x1 convolution with stride (the ResNet shortcut), no padding: x[n][h][w][c_in], w[c_out][c_in] ->
+ * y[n][(h-1)/stride+1][(w-1)/stride+1][c_out] = relu?(scale*conv + shift).  c_in a multiple of 16, at most
+ * 512; c_out a multiple of 64; scale / shift nullable; x, w, y, scale, shift 16-byte aligned. */
+int cg_pointwise_conv(const void* x, const void* w, const float* scale, const float* shift, void* y, int32_t n,
+                      int32_t h, int32_t wd, int32_t c_in, int32_t c_out, int32_t stride, int32_t relu,
+                      void* hip_stream);
 
 /* 3x3 max pooling, stride 2, padding 1 (the maximum runs over the taps inside the image):
  * x[n][h][w][c] -> y[n][(h-1)/2+1][(w-1)/2+1][c]; c a multiple of 8; x, y 16-byte aligned. */

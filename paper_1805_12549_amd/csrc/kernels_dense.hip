@@ -267,6 +267,78 @@ __global__ __launch_bounds__(256) void conv7x7s2c3_mfma_kernel(const uint16_t* _
   }   // tiles of the row
 }
 
+// 1x1 convolution with stride (the ResNet shortcut) on the matrix cores: a GEMM of the strided
+// pixels (column operand, 16 bytes per lane and K step straight from global memory: a pixel's
+// channels are contiguous) with the weights of a 64-channel block (row operand, laid out once
+// per block in LDS, rows permuted as in the kernel above).  Block = 128 output pixels x 64
+// channels, four wavefronts of 32 pixels each.
+__global__ __launch_bounds__(256) void pointwise_conv_kernel(const uint16_t* __restrict__ x, const uint16_t* __restrict__ w,
+                                                             const float* __restrict__ scale,
+                                                             const float* __restrict__ shift, uint16_t* __restrict__ y,
+                                                             long long m_total, int h, int wd, int c_in, int c_out,
+                                                             int stride, int ho, int wo, int relu) {
+  extern __shared__ __align__(16) uint16_t wlp[];          // [c_in/8 chunks][64 rows][8]
+  const int tid = threadIdx.x;
+  const int cb = blockIdx.y;
+  const int nq = c_in >> 3;
+  for (int i = tid; i < nq * kCb; i += 256) {
+    const int col = i / nq, q = i - col * nq;            // consecutive threads read consecutive 16-byte pieces
+    const int ch = col & 31;
+    const int row = (col & 32) + 8 * ((ch & 15) >> 2) + 4 * (ch >> 4) + (ch & 3);
+    *(uint4*)(wlp + ((q * kCb + row) << 3)) = *(const uint4*)(w + ((long long)(cb * kCb + col) * c_in + q * 8));
+  }
+  __syncthreads();
+  const int lane = tid & 63, wave = tid >> 6;
+  const int lj = lane & 31, lh = lane >> 5;
+  const long long m = (long long)blockIdx.x * 128 + wave * 32 + lj;
+  const bool valid = m < m_total;
+  const long long mm = valid ? m : 0;
+  const int ox = (int)(mm % wo);
+  const long long t2 = mm / wo;
+  const int oy = (int)(t2 % ho);
+  const long long img = t2 / ho;
+  const uint16_t* src = x + ((img * h + (long long)oy * stride) * wd + (long long)ox * stride) * c_in + lh * 8;
+  stem_f32x16 acc[2];
+#pragma unroll
+  for (int fc = 0; fc < 2; ++fc)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) acc[fc][i] = 0.0f;
+  const int steps = c_in >> 4;
+#pragma unroll 4
+  for (int st = 0; st < steps; ++st) {
+    stem_i32x4 b = {0, 0, 0, 0};
+    if (valid) b = *(const stem_i32x4*)(src + st * 16);
+    const int q = 2 * st + lh;
+#pragma unroll
+    for (int fc = 0; fc < 2; ++fc) {
+      const stem_i32x4 a = *(const stem_i32x4*)(wlp + ((q * kCb + 32 * fc + lj) << 3));
+      acc[fc] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(stem_bf16x8, a), __builtin_bit_cast(stem_bf16x8, b),
+                                                        acc[fc], 0, 0, 0);
+    }
+  }
+  if (!valid) return;
+#pragma unroll
+  for (int fc = 0; fc < 2; ++fc) {
+    const int co0 = cb * kCb + 32 * fc + 16 * lh;
+    uint16_t out[16];
+#pragma unroll
+    for (int q4 = 0; q4 < 4; ++q4) {
+      const float4 a4 = scale ? *(const float4*)(scale + co0 + 4 * q4) : float4{1.0f, 1.0f, 1.0f, 1.0f};
+      const float4 b4 = shift ? *(const float4*)(shift + co0 + 4 * q4) : float4{0.0f, 0.0f, 0.0f, 0.0f};
+      const float sc[4] = {a4.x, a4.y, a4.z, a4.w}, sh[4] = {b4.x, b4.y, b4.z, b4.w};
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        float v = acc[fc][4 * q4 + e] * sc[e] + sh[e];
+        if (relu) v = fmaxf(v, 0.0f);
+        out[4 * q4 + e] = float_to_bf16(v);
+      }
+    }
+    uint4* dst = (uint4*)(y + m * c_out + co0);
+    dst[0] = *(const uint4*)(out);
+    dst[1] = *(const uint4*)(out + 8);
+  }
+}
+
 // 3x3 stride-2 max pooling with padding 1: the maximum over the taps inside the image.
 // One thread per (output pixel, 8 channels).
 __global__ __launch_bounds__(256) void maxpool3x3s2_kernel(const uint16_t* __restrict__ x, uint16_t* __restrict__ y, int n,
@@ -390,6 +462,30 @@ int cg_small_cin_conv(const void* x, const void* w, const float* scale, const fl
                      c_in, c_out, k, stride, pad, ho, wo, relu);
   const hipError_t e = hipGetLastError();
   if (e != hipSuccess) return cg::set_error(CG_EHIP, "cg_small_cin_conv: %s", hipGetErrorString(e));
+  return CG_OK;
+}
+
+int cg_pointwise_conv(const void* x, const void* w, const float* scale, const float* shift, void* y, int32_t n,
+                      int32_t h, int32_t wd, int32_t c_in, int32_t c_out, int32_t stride, int32_t relu,
+                      void* hip_stream) {
+  if (!x || !w || !y) return cg::set_error(CG_EINVAL, "cg_pointwise_conv: x, w and y must not be NULL");
+  if (n < 0 || h <= 0 || wd <= 0) return cg::set_error(CG_EINVAL, "cg_pointwise_conv: bad image size");
+  if (stride < 1) return cg::set_error(CG_EINVAL, "cg_pointwise_conv: stride must be >= 1");
+  if (c_in <= 0 || c_in % 16 || c_in > 512)
+    return cg::set_error(CG_EUNSUPPORTED, "cg_pointwise_conv: c_in must be a multiple of 16, at most 512");
+  if (c_out <= 0 || c_out % kCb) return cg::set_error(CG_EUNSUPPORTED, "cg_pointwise_conv: c_out must be a multiple of 64");
+  if ((((uintptr_t)x) | ((uintptr_t)w) | ((uintptr_t)y) | ((uintptr_t)scale) | ((uintptr_t)shift)) & 15)
+    return cg::set_error(CG_EINVAL, "cg_pointwise_conv: x, w, y, scale and shift must be 16-byte aligned");
+  if (n == 0) return CG_OK;
+  const int ho = (h - 1) / stride + 1, wo = (wd - 1) / stride + 1;
+  const long long m_total = (long long)n * ho * wo;
+  const long long blocks = (m_total + 127) / 128;
+  if (blocks > 0x7fffffffll) return cg::set_error(CG_EUNSUPPORTED, "cg_pointwise_conv: too large");
+  hipLaunchKernelGGL(pointwise_conv_kernel, dim3((unsigned)blocks, (unsigned)(c_out / kCb)), dim3(256),
+                     (size_t)c_in * kCb * 2, (hipStream_t)hip_stream, (const uint16_t*)x, (const uint16_t*)w, scale, shift,
+                     (uint16_t*)y, m_total, h, wd, c_in, c_out, stride, ho, wo, relu);
+  const hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return cg::set_error(CG_EHIP, "cg_pointwise_conv: %s", hipGetErrorString(e));
   return CG_OK;
 }
 

@@ -1,7 +1,7 @@
 """A channel-gated ResNet-18 forward pass assembled from the C-ABI entry points.
 
 Orchestration only: every layer runs in the HIP library (input convolution, max pooling, sixteen
-gated 3x3 convolutions with fused scale/shift / residual / ReLU, three dense 1x1 stride-2 shortcut
+gated 3x3 convolutions with fused scale/shift / residual / ReLU, three 1x1 stride-2 shortcut
 convolutions, average pooling + fully connected layer).  Weights are random (there is no trained
 network here); scale/shift pairs and gate statistics are calibrated on a few synthetic images so
 that activations keep a stable range and about a fraction `rho` of the gates fire in every layer.
@@ -47,6 +47,25 @@ def conv_specs(size: int) -> List[ConvSpec]:
             specs.append(ConvSpec("l%d.%d.b" % (stage + 1, blk), c_out, c_out, hw, 1, True, True))
             c = c_out
     return specs
+
+
+class _Shortcut:
+    """A block's 1x1 stride-2 shortcut convolution with its scale/shift (cg_pointwise_conv)."""
+
+    def __init__(self, spec, w, scale, shift):
+        self.spec, self.w, self.scale, self.shift = spec, w, scale, shift
+
+    def forward(self, x, bitmap=False, counts=False):
+        s = self.spec
+        n = x.shape[0]
+        ho = (s.hw - 1) // 2 + 1
+        y = torch.empty((n, ho, ho, s.c_out), dtype=torch.bfloat16, device=x.device)
+        B.cg_pointwise_conv(x.data_ptr(), self.w.data_ptr(), self.scale.data_ptr(), self.shift.data_ptr(), y.data_ptr(),
+                            n, s.hw, s.hw, s.c_in, s.c_out, 2, False, torch.cuda.current_stream().cuda_stream)
+        return y, None, None
+
+    def close(self):
+        pass
 
 
 def _t(a, dtype=torch.bfloat16):
@@ -106,10 +125,7 @@ class GatedResNet18:
                            scale1=scale, shift1=shift, **kw)
 
     def _make_shortcut(self, spec: ConvSpec, w, scale, shift, n_max):
-        return B.GatedConv(n_max=n_max, h=spec.hw, w=spec.hw, c_in=spec.c_in, c_out=spec.c_out, c_base=spec.c_in,
-                           w_base=_t(w), w_cond=None, in_dtype=B.CG_BF16, out_dtype=B.CG_BF16, kh=1, kw=1,
-                           stride=2, pad=0, epilogue=B.CG_EPI_AFFINE, scale0=scale, shift0=shift, scale1=scale,
-                           shift1=shift)
+        return _Shortcut(spec, _t(w), _t(scale, torch.float32), _t(shift, torch.float32))
 
     # -- calibration: scale/shift and gate statistics from a few synthetic images ---------------------
     @staticmethod

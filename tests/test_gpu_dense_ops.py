@@ -92,6 +92,28 @@ def test_shortcut_conv_1x1_stride2_dense(c_in, c_out, hw):
     assert rep.variant == B.CG_VARIANT_MFMA and rep.fired_frac == 0.0
 
 
+@pytest.mark.parametrize("n,hw,c_in,c_out,stride", [(2, 56, 64, 128, 2), (3, 28, 128, 256, 2), (2, 14, 256, 512, 2),
+                                                    (1, 9, 16, 64, 1), (2, 7, 512, 64, 3)])
+def test_pointwise_conv(n, hw, c_in, c_out, stride):
+    rng = np.random.default_rng(c_in + hw)
+    x = _bf16(rng.standard_normal((n, hw, hw + 1, c_in)))
+    wt = _bf16(rng.standard_normal((c_out, 1, 1, c_in)) * np.sqrt(2.0 / c_in))
+    sc = rng.uniform(0.5, 1.5, c_out).astype(np.float32)
+    sh = (rng.standard_normal(c_out) * 0.1).astype(np.float32)
+    ho, wo = (hw - 1) // stride + 1, hw // stride + 1
+    xd, wd_, scd, shd = _dev(x), _dev(wt.reshape(c_out, c_in)), _dev(sc, torch.float32), _dev(sh, torch.float32)
+    for relu, aff in ((True, True), (False, False)):
+        y = torch.empty((n, ho, wo, c_out), dtype=torch.bfloat16, device="cuda")
+        B.cg_pointwise_conv(xd.data_ptr(), wd_.data_ptr(), scd.data_ptr() if aff else 0, shd.data_ptr() if aff else 0,
+                            y.data_ptr(), n, hw, hw + 1, c_in, c_out, stride, relu, _stream())
+        torch.cuda.synchronize()
+        ref = O.dense_conv(x, wt, stride=stride, pad=0, scale=sc if aff else None, shift=sh if aff else None, relu=relu)
+        assert ref.shape == (n, ho, wo, c_out)
+        got = y.float().cpu().numpy().astype(np.float64)
+        tol = P.ATOL + P.RTOL * np.abs(ref) + P.bf16_ulp(ref)
+        assert (np.abs(got - ref) <= tol).all(), float(np.abs(got - ref).max())
+
+
 def test_dense_ops_reject_bad_arguments_before_any_launch():
     with pytest.raises(B.CGError) as e:
         B.cg_small_cin_conv(16, 16, 0, 0, 16, 1, 8, 8, 5, 64, 3, 1, 1, True)
