@@ -97,13 +97,28 @@ __device__ __forceinline__ void finish8(const Params& p, i32x4 s0, i32x4 s1, uin
         for (int k = 0; k < 8; ++k) res[k] = bf16_to_float(rb[k]);
       }
     }
+    // the two scale/shift pairs of the eight channels as 16-byte loads (co0 is a multiple of 8)
+    float sc0[8], sh0[8], sc1[8], sh1[8];
+    if (p.epilogue & CG_EPI_AFFINE) {
+#pragma unroll
+      for (int h4 = 0; h4 < 2; ++h4) {
+        const f32x4 a0 = *(const f32x4*)(p.sc0 + co0 + 4 * h4), b0 = *(const f32x4*)(p.sh0 + co0 + 4 * h4);
+        const f32x4 a1 = *(const f32x4*)(p.sc1 + co0 + 4 * h4), b1 = *(const f32x4*)(p.sh1 + co0 + 4 * h4);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          sc0[4 * h4 + e] = a0[e];
+          sh0[4 * h4 + e] = b0[e];
+          sc1[4 * h4 + e] = a1[e];
+          sh1[4 * h4 + e] = b1[e];
+        }
+      }
+    }
 #pragma unroll
     for (int k = 0; k < 8; ++k) {
       const float s = __int_as_float(k < 4 ? s0[k] : s1[k - 4]);
       const bool f = p.gated ? ((dbyte >> k) & 1u) : true;
-      const int co = co0 + k;
       float a = s;
-      if (p.epilogue & CG_EPI_AFFINE) a = f ? fmaf(p.sc1[co], s, p.sh1[co]) : fmaf(p.sc0[co], s, p.sh0[co]);
+      if (p.epilogue & CG_EPI_AFFINE) a = f ? fmaf(sc1[k], s, sh1[k]) : fmaf(sc0[k], s, sh0[k]);
       if (p.epilogue & CG_EPI_RESIDUAL) a += res[k];
       if (p.epilogue & CG_EPI_RELU) a = fmaxf(a, 0.0f);
       v[k] = a;
