@@ -229,7 +229,7 @@ __global__ __launch_bounds__(NWV * 64, 2) void gated_conv_rows_kernel(
   // K steps the MFMA operands are read ahead (reading three ahead measured no faster on any layer)
   constexpr int PD = 1;
   constexpr int BM = 32 * NF * NPW;            // pixels per tile
-  constexpr int TAB = BM * 18 + 512;           // bytes of tables
+  constexpr int TAB = BM * 18 + 512 + 1024;    // bytes of tables
 
   // two patch buffers, the weight granule ring, tables
   __shared__ __align__(1024) char pat2[2 * PB];
@@ -241,6 +241,7 @@ __global__ __launch_bounds__(NWV * 64, 2) void gated_conv_rows_kernel(
   uint16_t* rank = (uint16_t*)(bmp + 2 * BM);    // [BM] tile pixel -> compacted position
   acc_t* tlo = (acc_t*)(rank + BM);              // [64] thresholds of this channel block
   acc_t* thi = tlo + 64;
+  float* aff = (float*)(thi + 64);               // [4][64] scale0, shift0, scale1, shift1 of this channel block
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -383,6 +384,13 @@ __global__ __launch_bounds__(NWV * 64, 2) void gated_conv_rows_kernel(
   if (tid < 64) {
     tlo[tid] = my_lo;
     thi[tid] = my_hi;
+    if (Base::kDtype != CG_I8 && (p.epilogue & CG_EPI_AFFINE)) {
+      const int co = cbk * kBn + tid;
+      aff[tid] = p.sc0[co];
+      aff[64 + tid] = p.sh0[co];
+      aff[128 + tid] = p.sc1[co];
+      aff[192 + tid] = p.sh1[co];
+    }
   }
 
   acc16 accP[NF][NC], accR[NF][NC];
@@ -708,6 +716,7 @@ __global__ __launch_bounds__(NWV * 64, 2) void gated_conv_rows_kernel(
     const int rs = rb + 16;             // skewed row stride in LDS
     const bool lean = Base::kDtype != CG_I8 && p.out_dtype == CG_BF16 &&
                       !(p.epilogue & (CG_EPI_AFFINE | CG_EPI_RESIDUAL));
+    const bool fastaff = Base::kDtype != CG_I8 && p.out_dtype == CG_BF16 && (p.epilogue & CG_EPI_AFFINE);
     const float relu_lo = (p.epilogue & CG_EPI_RELU) ? 0.0f : -__builtin_inff();
     static_assert(32 * NPW * 144 <= 2 * PB, "output tile must fit the patch buffers");
 #pragma unroll
@@ -740,6 +749,37 @@ __global__ __launch_bounds__(NWV * 64, 2) void gated_conv_rows_kernel(
                               ((uint32_t)float_to_bf16(fmaxf(__int_as_float(v[e >> 1][2 * (e & 1) + 1]), relu_lo)) << 16));
                 o2[e] = (int)((uint32_t)float_to_bf16(fmaxf(__int_as_float(v[2 + (e >> 1)][2 * (e & 1)]), relu_lo)) |
                               ((uint32_t)float_to_bf16(fmaxf(__int_as_float(v[2 + (e >> 1)][2 * (e & 1) + 1]), relu_lo)) << 16));
+              }
+            }
+          } else if (fastaff) {
+            // bf16 output with scale/shift by decision (tables in LDS), optional residual and ReLU
+            if constexpr (Base::kDtype != CG_I8) {
+              uint16_t res[16];
+#pragma unroll
+              for (int i = 0; i < 16; ++i) res[i] = 0;
+              if ((p.epilogue & CG_EPI_RESIDUAL) && pval[fp]) {
+                *(i32x4*)(res) = *(const i32x4*)((const uint16_t*)p.residual + o);
+                *(i32x4*)(res + 8) = *(const i32x4*)((const uint16_t*)p.residual + o + 8);
+              }
+              float r16[16];
+#pragma unroll
+              for (int q4 = 0; q4 < 4; ++q4) {
+                const f32x4 a0 = *(const f32x4*)(aff + cl + 4 * q4), b0 = *(const f32x4*)(aff + 64 + cl + 4 * q4);
+                const f32x4 a1 = *(const f32x4*)(aff + 128 + cl + 4 * q4), b1 = *(const f32x4*)(aff + 192 + cl + 4 * q4);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                  const int i = 4 * q4 + e;
+                  const float sv = __int_as_float(v[q4][e]);
+                  const bool f = p.gated ? ((d16 >> i) & 1u) != 0u : true;
+                  float a = f ? fmaf(a1[e], sv, b1[e]) : fmaf(a0[e], sv, b0[e]);
+                  if (p.epilogue & CG_EPI_RESIDUAL) a += bf16_to_float(res[i]);
+                  r16[i] = fmaxf(a, relu_lo);
+                }
+              }
+#pragma unroll
+              for (int e = 0; e < 4; ++e) {
+                o0[e] = (int)((uint32_t)float_to_bf16(r16[2 * e]) | ((uint32_t)float_to_bf16(r16[2 * e + 1]) << 16));
+                o2[e] = (int)((uint32_t)float_to_bf16(r16[8 + 2 * e]) | ((uint32_t)float_to_bf16(r16[8 + 2 * e + 1]) << 16));
               }
             }
           } else if (pval[fp]) {
