@@ -45,6 +45,8 @@ def parse():
                     help="kernel family (auto = what the library picks)")
     ap.add_argument("--dtype", default="bf16", choices=["bf16", "int8"],
                     help="bf16 (the headline workload) or int8 (int8 activations/weights, int32 sums, int8 requantised output)")
+    ap.add_argument("--fused-epilogue", action="store_true",
+                    help="scale/shift by decision + residual add + ReLU in the layer epilogue (bf16) instead of ReLU alone")
     ap.add_argument("--grouped", action="store_true",
                     help="channel grouping (output group i takes input group i as its base path) instead of the "
                          "default fixed base channels")
@@ -105,6 +107,13 @@ def main():
         common = dict(n_max=s.n, h=s.h, w=s.w, c_in=s.c_in, c_out=s.c_out, in_dtype=B.CG_I8 if i8 else B.CG_BF16,
                       out_dtype=B.CG_I8 if i8 else B.CG_BF16, stride=s.stride, pad=s.pad, epilogue=B.CG_EPI_RELU,
                       variant=variant)
+        res = None
+        if args.fused_epilogue and not i8:
+            erng = np.random.default_rng(1000 + li)
+            common.update(epilogue=B.CG_EPI_RELU | B.CG_EPI_AFFINE | B.CG_EPI_RESIDUAL,
+                          scale0=erng.uniform(0.5, 1.5, s.c_out), shift0=erng.normal(0, 0.1, s.c_out),
+                          scale1=erng.uniform(0.5, 1.5, s.c_out), shift1=erng.normal(0, 0.1, s.c_out))
+            res = torch.randn((s.n, s.ho, s.wo, s.c_out), device=dev).to(torch.bfloat16)
         if i8:
             common.update(rq)
             gkw = dict(gate_thr_i32=gate)
@@ -113,7 +122,7 @@ def main():
         gated = B.GatedConv(c_base=s.c_base, w_base=wb, w_cond=wc, groups=s.groups if args.grouped else 0,
                             tau_c=args.tau_c, **gkw, **common)
         dense = None if args.no_dense else B.GatedConv(c_base=s.c_in, w_base=wfull, w_cond=None, **common)
-        layers.append(dict(shape=s, inp=inp, gate=gate, xs=xs, ys=ys, bms=bms, gated=gated, dense=dense, nset=nset,
+        layers.append(dict(shape=s, inp=inp, gate=gate, xs=xs, ys=ys, bms=bms, gated=gated, dense=dense, nset=nset, res=res,
                            rq=rq if i8 else None))
     torch.cuda.synchronize()
     t_gen = time.perf_counter() - t_gen
@@ -121,7 +130,7 @@ def main():
     # ---- firing rate and executed-block fraction (one untimed call with counts on) ----------
     for L in layers:
         s = L["shape"]
-        _, bm, cnt = L["gated"].forward(L["xs"][0], y=L["ys"][0], bitmap=L["bms"][0], counts=True)
+        _, bm, cnt = L["gated"].forward(L["xs"][0], residual=L["res"], y=L["ys"][0], bitmap=L["bms"][0], counts=True)
         torch.cuda.synchronize()
         c = cnt.cpu().numpy().view(np.uint32)
         fired = int(c[0]) | (int(c[1]) << 32)
@@ -132,7 +141,8 @@ def main():
 
     def run_layer(L, which, k):
         i = k % L["nset"]
-        L[which].forward(L["xs"][i], y=L["ys"][i], bitmap=L["bms"][i] if which == "gated" else False, counts=False)
+        L[which].forward(L["xs"][i], residual=L["res"], y=L["ys"][i], bitmap=L["bms"][i] if which == "gated" else False,
+                         counts=False)
 
     # ---- per-layer timing with events on the launch stream ----------------------------------
     def time_layer(L, which, rounds=3):
@@ -288,6 +298,7 @@ def main():
                                "%s gate maps, target firing %.2f%s; step = all %d layers" %
                                (args.batch, args.dtype, args.kind, args.rho,
                                 (", channel grouping" if args.grouped else "") +
+                                (", fused scale/shift + residual + ReLU epilogue" if args.fused_epilogue else "") +
                                 (", channel-wise gate tau_c=%.2f" % args.tau_c if args.tau_c > 0 else ""), len(layers)),
                    "launch": "hip graph replay" if graph is not None else "eager",
                    "sum_us_gated": round(t_kernel_us, 2),
