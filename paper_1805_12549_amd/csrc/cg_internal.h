@@ -127,6 +127,7 @@ struct Mfma3Plan {
   int nf;                  // 32-pixel fragments per wavefront in the base phase
   int nc;                  // 32-channel fragments per wavefront: 2, or 1 when two wavefronts share a pixel fragment
   int ldw;                 // wavefronts (of nwv) that only issue the LDS-direct loads: 0 or 4
+  int xcd_cb;              // 1: blocks of one channel block share an XCD (needs n_cb % 8 == 0); 0: blocks of one tile do
   int bm;                  // 32*nf*nwv*nc/2 pixels per tile, padded
   int n_cb;                // c_out / 64
   int tr;                  // global output rows per tile
