@@ -254,7 +254,8 @@ __global__ __launch_bounds__(NWV * 64, 2) void gated_conv_rows_kernel(
   const int lj = lane & 31, lh = lane >> 5;
 
   // Block id mod 8 is the XCD.  Normally the blocks that share a pixel tile (different channel blocks)
-  // sit on one XCD, so the tile's input is fetched into one L2.  xcd_cb: the blocks that share a
+  // sit on one XCD, and an XCD takes a contiguous run of tiles, so a tile's input and the halo rows it
+  // shares with its neighbours are fetched into one L2.  xcd_cb: the blocks that share a
   // channel block sit on one XCD instead, so that each L2 holds an eighth of the weights (layers whose
   // weights outweigh their input).
   int tile, cbk;
@@ -267,7 +268,8 @@ __global__ __launch_bounds__(NWV * 64, 2) void gated_conv_rows_kernel(
     } else {
       const int grp = slot / g.n_cb;
       cbk = slot - grp * g.n_cb;
-      tile = grp * 8 + xcd;
+      const int tiles = (p.n * p.ho + g.tr - 1) / g.tr;
+      tile = xcd * ((tiles + 7) >> 3) + grp;        // an XCD takes a contiguous run of tiles: neighbours share halo rows in its L2
     }
   }
   const int total_rows = p.n * p.ho;
