@@ -297,10 +297,20 @@ __global__ __launch_bounds__(NWV * 64, 2) void gated_conv_rows_kernel(
   // sits at wbase0 + j*GB in the base phase and at wcond0 + (j - 3*S0)*GB in the conditional phase
   const char* const wbase0 = wpk0 + (size_t)cbk * 3 * g.stages[0] * GB;
   const char* const wcond0 = wpk1 + (size_t)cbk * 3 * g.stages[1] * GB;
-  // weight load instruction u of this loading wavefront: 1 KB number lw + NLW*u of the granule
+  // weight load instruction u of this loading wavefront: 1 KB number lw*WPW + u of the granule
+  // (a loading wavefront takes WPW consecutive pieces: one address pair and immediate offsets)
+  static_assert(WPW <= 3, "immediate offsets below 4 KB");
   auto issue_w = [&](const char* ws, char* dst, int u) __attribute__((always_inline)) {
-    const int idx = lw + NLW * u;
-    if (idx < 2 * GK) lds_direct16(ws + idx * 1024 + lane * 16, dst + idx * 1024);
+    const int idx = lw * WPW + u;
+    if (idx < 2 * GK) {
+      const auto* gp = (const __attribute__((address_space(1))) void*)(ws + lw * (WPW * 1024) + lane * 16);
+      auto* lp = (__attribute__((address_space(3))) void*)(dst + lw * (WPW * 1024));
+      switch (u) {
+        case 0: __builtin_amdgcn_global_load_lds(gp, lp, 16, 0, 0); break;
+        case 1: __builtin_amdgcn_global_load_lds(gp, lp, 16, 1024, 0); break;
+        default: __builtin_amdgcn_global_load_lds(gp, lp, 16, 2048, 0); break;
+      }
+    }
   };
   if (is_ld) {
 #pragma unroll
