@@ -393,9 +393,7 @@ MfmaPlan mfma_plan(const cg_conv_desc& d) {
   if ((long long)d.n_max * d.h * d.w >= (1ll << 31) / 2 || (long long)d.n_max * ho * wo >= (1ll << 31) / 2) return g;
   // residual / output vector accesses need 8-channel groups: c_out % 64 covers it
 
-  const char* env_bn = getenv("CG_MFMA_BN");
   g.bn = 64;
-  if (env_bn && atoi(env_bn) == 128 && d.c_out % 128 == 0) g.bn = 128;
   g.n_cb = d.c_out / g.bn;
   g.taps = d.kh * d.kw;
 

@@ -588,14 +588,10 @@ Mfma2Plan mfma2_plan(const cg_conv_desc& d) {
   const bool gated = c_cond > 0;
   const int cq0 = d.c_base / g.ch, cq1 = c_cond / g.ch;
 
-  const char* env_ngw = getenv("CG_MFMA2_NGW");
-  const char* env_cbq = getenv("CG_MFMA2_CBQ");
   const long long rows = (long long)d.n_max * ho;
   for (int cbq = 4; cbq >= 1; cbq >>= 1) {
-    if (env_cbq && atoi(env_cbq) != cbq) continue;
     if (cq0 % cbq || (gated && cq1 % cbq)) continue;
     for (int ngw = 2; ngw >= 1; --ngw) {
-      if (env_ngw && atoi(env_ngw) != ngw) continue;
       g.ngw = ngw;
       g.bm = ngw * 16 * kWaves;
       g.tr = g.bm / wo;
