@@ -599,7 +599,7 @@ Mfma2Plan mfma2_plan(const cg_conv_desc& d) {
       if (g.tr > rows) g.tr = (int)rows;
       const long long tiles = (rows + g.tr - 1) / g.tr;
       // prefer the large tile only when it still fills the 256 CUs
-      if (ngw == 2 && !env_ngw && tiles * g.n_cb < 256) continue;
+      if (ngw == 2 && tiles * g.n_cb < 256) continue;
       g.bm_valid = g.tr * wo;
       g.ng = (g.bm_valid + 15) / 16;
       int pr = 0;
