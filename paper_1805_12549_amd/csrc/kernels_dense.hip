@@ -411,9 +411,19 @@ __global__ __launch_bounds__(1024) void avgpool_fc_kernel(const uint16_t* __rest
   __syncthreads();
   // one wavefront per class: lanes stride over the channels, then a butterfly sum
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
+  const bool vec = (c & 7) == 0 && (((uintptr_t)wfc) & 15) == 0;     // a lane takes eight consecutive channels per load
   for (int k = k0 + wave; k < k1; k += nw) {
     float s = 0.0f;
-    for (int ch = lane; ch < c; ch += 64) s = fmaf(bf16_to_float(wfc[(long long)k * c + ch]), mean[ch], s);
+    if (vec) {
+      for (int ch = lane * 8; ch < c; ch += 512) {
+        uint16_t wv[8];
+        *(uint4*)wv = *(const uint4*)(wfc + (long long)k * c + ch);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) s = fmaf(bf16_to_float(wv[e]), mean[ch + e], s);
+      }
+    } else {
+      for (int ch = lane; ch < c; ch += 64) s = fmaf(bf16_to_float(wfc[(long long)k * c + ch]), mean[ch], s);
+    }
 #pragma unroll
     for (int sft = 32; sft >= 1; sft >>= 1) s += __shfl_xor(s, sft, 64);
     if (lane == 0) logits[(long long)img * classes + k] = s + (bias ? bias[k] : 0.0f);
