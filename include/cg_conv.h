@@ -185,6 +185,13 @@ int cg_small_cin_conv(const void* x, const void* w, const float* scale, const fl
                       int32_t h, int32_t wd, int32_t c_in, int32_t c_out, int32_t k, int32_t stride, int32_t pad,
                       int32_t relu, void* hip_stream);
 
+/* The ImageNet input layer and the max pooling behind it in one kernel: 7x7 stride-2 convolution of
+ * x[n][h][w][3] with w[c_out][7][7][3] (zero padding pad), scale/shift/ReLU as above, then 3x3 stride-2
+ * max pooling with padding 1; only the pooled tensor y[n][(ho-1)/2+1][(wo-1)/2+1][c_out] is written
+ * (ho, wo = the convolution's output size).  Equal to cg_small_cin_conv followed by cg_maxpool3x3s2. */
+int cg_conv7x7s2_maxpool(const void* x, const void* w, const float* scale, const float* shift, void* y, int32_t n,
+                         int32_t h, int32_t wd, int32_t c_out, int32_t pad, int32_t relu, void* hip_stream);
+
 /* 1x1 convolution with stride (the ResNet shortcut), no padding: x[n][h][w][c_in], w[c_out][c_in] ->
  * y[n][(h-1)/stride+1][(w-1)/stride+1][c_out] = relu?(scale*conv + shift).  c_in a multiple of 16, at most
  * 512; c_out a multiple of 64; scale / shift nullable; x, w, y, scale, shift 16-byte aligned. */

@@ -49,7 +49,7 @@ CG_EPI_RELU, CG_EPI_AFFINE, CG_EPI_RESIDUAL = 1, 2, 4
 CG_VARIANT_AUTO, CG_VARIANT_NAIVE, CG_VARIANT_MFMA, CG_VARIANT_MFMA_COMPACT, CG_VARIANT_MFMA_ROWS = 0, 1, 2, 3, 4
 
 EXPORTS = ("cg_conv_packed_bytes", "cg_conv_create", "cg_conv_workspace_bytes", "cg_conv_forward",
-           "cg_conv_destroy", "cg_conv_info", "cg_last_error", "cg_small_cin_conv", "cg_pointwise_conv",
+           "cg_conv_destroy", "cg_conv_info", "cg_last_error", "cg_small_cin_conv", "cg_conv7x7s2_maxpool", "cg_pointwise_conv",
            "cg_maxpool3x3s2", "cg_avgpool_fc")
 
 _pf = C.POINTER(C.c_float)
@@ -93,6 +93,8 @@ _lib.cg_last_error.argtypes = []
 _lib.cg_last_error.restype = C.c_char_p
 _lib.cg_small_cin_conv.argtypes = [C.c_void_p] * 5 + [C.c_int32] * 9 + [C.c_void_p]
 _lib.cg_small_cin_conv.restype = C.c_int
+_lib.cg_conv7x7s2_maxpool.argtypes = [C.c_void_p] * 5 + [C.c_int32] * 6 + [C.c_void_p]
+_lib.cg_conv7x7s2_maxpool.restype = C.c_int
 _lib.cg_pointwise_conv.argtypes = [C.c_void_p] * 5 + [C.c_int32] * 7 + [C.c_void_p]
 _lib.cg_pointwise_conv.restype = C.c_int
 _lib.cg_maxpool3x3s2.argtypes = [C.c_void_p, C.c_void_p] + [C.c_int32] * 4 + [C.c_void_p]
@@ -152,6 +154,12 @@ def cg_small_cin_conv(x: int, w: int, scale: int, shift: int, y: int, n: int, h:
     """Raw device addresses (0 = NULL for scale / shift)."""
     _check(_lib.cg_small_cin_conv(C.c_void_p(x), C.c_void_p(w), C.c_void_p(scale), C.c_void_p(shift), C.c_void_p(y),
                                   n, h, wd, c_in, c_out, k, stride, pad, int(bool(relu)), C.c_void_p(hip_stream)))
+
+
+def cg_conv7x7s2_maxpool(x: int, w: int, scale: int, shift: int, y: int, n: int, h: int, wd: int, c_out: int,
+                         pad: int, relu: bool, hip_stream: int = 0) -> None:
+    _check(_lib.cg_conv7x7s2_maxpool(C.c_void_p(x), C.c_void_p(w), C.c_void_p(scale), C.c_void_p(shift), C.c_void_p(y),
+                                     n, h, wd, c_out, pad, int(bool(relu)), C.c_void_p(hip_stream)))
 
 
 def cg_pointwise_conv(x: int, w: int, scale: int, shift: int, y: int, n: int, h: int, wd: int, c_in: int, c_out: int,

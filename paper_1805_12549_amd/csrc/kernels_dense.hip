@@ -128,6 +128,13 @@ typedef __attribute__((ext_vector_type(8))) __bf16 stem_bf16x8;
 typedef __attribute__((ext_vector_type(16))) float stem_f32x16;
 typedef __attribute__((ext_vector_type(4))) int stem_i32x4;
 
+//
+// POOL: the 3x3 stride-2 max pooling (padding 1) that follows the layer in a ResNet is applied in
+// the block: the 16x16 tile then starts one row and column before an even position and yields the
+// 7x7 pooled pixels whose windows it holds (neighbouring tiles overlap by two rows / columns); the
+// converted outputs meet in an LDS tile, positions outside the layer's output count as -inf, and
+// only the pooled tensor is written.
+template <bool POOL>
 __global__ __launch_bounds__(256) void conv7x7s2c3_mfma_kernel(const uint16_t* __restrict__ x,
                                                                const uint16_t* __restrict__ w,
                                                                const float* __restrict__ scale,
@@ -141,9 +148,13 @@ __global__ __launch_bounds__(256) void conv7x7s2c3_mfma_kernel(const uint16_t* _
   constexpr int NQ = 22;                           // 8-element K chunks
   __shared__ __align__(16) uint16_t wl[NQ * kCb * 8];    // [chunk][row][8]
   __shared__ __align__(16) uint16_t xl[PROWS * PR];
+  __shared__ __align__(16) uint16_t ol[POOL ? TILE * TILE * kCb : 8];   // [tile pixel][64 channels] (POOL)
+  constexpr int PT = 7;                            // pooled rows / columns per tile (POOL)
+  const int pho = (ho - 1) / 2 + 1, pwo = (wo - 1) / 2 + 1;   // pooled output size (POOL)
   const int tid = threadIdx.x;
   // one block walks tpb tiles of a row: the weights are laid out once per block
-  const int tiles_w = (wo + TILE - 1) / TILE, tiles_h = (ho + TILE - 1) / TILE;
+  const int tiles_w = POOL ? (pwo + PT - 1) / PT : (wo + TILE - 1) / TILE;
+  const int tiles_h = POOL ? (pho + PT - 1) / PT : (ho + TILE - 1) / TILE;
   const int strips = (tiles_w + tpb - 1) / tpb;
   int b = blockIdx.x;
   const int tw0 = (b % strips) * tpb;
@@ -186,7 +197,8 @@ __global__ __launch_bounds__(256) void conv7x7s2c3_mfma_kernel(const uint16_t* _
   for (int tw = tw0; tw < tw1; ++tw) {
   if (tw > tw0) __syncthreads();                   // the previous tile's patch has been read
   // input patch as bf16, zero outside the image and in the padding
-  const int h0 = th * TILE * ST - pad, w0 = tw * TILE * ST - pad;
+  const int oy0 = POOL ? 2 * PT * th - 1 : th * TILE, ox0 = POOL ? 2 * PT * tw - 1 : tw * TILE;   // the tile's first output pixel
+  const int h0 = oy0 * ST - pad, w0 = ox0 * ST - pad;
   // a thread fills one patch pixel (three channels) at a time; 40 pixel positions per row, the ones
   // past the patch edge or outside the image are zero
   constexpr int PPR = PR / CI;
@@ -239,8 +251,9 @@ __global__ __launch_bounds__(256) void conv7x7s2c3_mfma_kernel(const uint16_t* _
   }
 #pragma unroll
   for (int fp = 0; fp < 2; ++fp) {
-    const int oy = th * TILE + 2 * (2 * wave + fp) + (lj >> 4), ox = tw * TILE + (lj & 15);
-    if (oy >= ho || ox >= wo) continue;
+    const int oy = oy0 + 2 * (2 * wave + fp) + (lj >> 4), ox = ox0 + (lj & 15);
+    const bool inside = oy >= 0 && oy < ho && ox >= 0 && ox < wo;
+    if (!POOL && !inside) continue;
 #pragma unroll
     for (int fc = 0; fc < 2; ++fc) {
       const int co0 = cb * kCb + 32 * fc + 16 * lh;
@@ -257,11 +270,39 @@ __global__ __launch_bounds__(256) void conv7x7s2c3_mfma_kernel(const uint16_t* _
       for (int i = 0; i < 16; ++i) {
         float v = acc[fp][fc][i] * sc[i] + sh[i];
         if (relu) v = fmaxf(v, 0.0f);
-        out[i] = float_to_bf16(v);
+        out[i] = (POOL && !inside) ? (uint16_t)0xFF80 : float_to_bf16(v);     // 0xFF80 = -inf
       }
-      uint4* dst = (uint4*)(y + (((long long)img * ho + oy) * wo + ox) * c_out + co0);
+      uint4* dst = POOL ? (uint4*)(ol + ((2 * (2 * wave + fp) + (lj >> 4)) * TILE + (lj & 15)) * kCb + 32 * fc + 16 * lh)
+                        : (uint4*)(y + (((long long)img * ho + oy) * wo + ox) * c_out + co0);
       dst[0] = *(const uint4*)(out);
       dst[1] = *(const uint4*)(out + 8);
+    }
+  }
+  if constexpr (POOL) {
+    __syncthreads();
+    // pooled pixel (py, px) of the tile takes tile rows 2py .. 2py+2 and columns 2px .. 2px+2; a thread
+    // takes eight channels of one pooled pixel at a time
+    for (int it = tid; it < PT * PT * (kCb / 8); it += 256) {
+      const int c8 = it & 7, pp = it >> 3;
+      const int py = pp / PT, px = pp - py * PT;
+      const int gy = PT * th + py, gx = PT * tw + px;
+      if (gy >= pho || gx >= pwo) continue;
+      float m[8];
+#pragma unroll
+      for (int i = 0; i < 8; ++i) m[i] = -__builtin_inff();
+#pragma unroll
+      for (int r = 0; r < 3; ++r)
+#pragma unroll
+        for (int c = 0; c < 3; ++c) {
+          uint16_t v[8];
+          *(uint4*)v = *(const uint4*)(ol + ((2 * py + r) * TILE + 2 * px + c) * kCb + c8 * 8);
+#pragma unroll
+          for (int i = 0; i < 8; ++i) m[i] = fmaxf(m[i], bf16_to_float(v[i]));
+        }
+      uint16_t o8[8];
+#pragma unroll
+      for (int i = 0; i < 8; ++i) o8[i] = float_to_bf16(m[i]);
+      *(uint4*)(y + (((long long)img * pho + gy) * pwo + gx) * c_out + cb * kCb + c8 * 8) = *(const uint4*)o8;
     }
   }
   }   // tiles of the row
@@ -456,7 +497,7 @@ int cg_small_cin_conv(const void* x, const void* w, const float* scale, const fl
     const int tpb = rows16 >= 512 ? tiles_w16 : 1;
     const long long t16 = (long long)n * ((ho + 15) / 16) * ((tiles_w16 + tpb - 1) / tpb);
     if (t16 > 0x7fffffffll) return cg::set_error(CG_EUNSUPPORTED, "cg_small_cin_conv: too many tiles");
-    hipLaunchKernelGGL(conv7x7s2c3_mfma_kernel, dim3((unsigned)t16, (unsigned)(c_out / kCb)), dim3(256), 0,
+    hipLaunchKernelGGL(conv7x7s2c3_mfma_kernel<false>, dim3((unsigned)t16, (unsigned)(c_out / kCb)), dim3(256), 0,
                        (hipStream_t)hip_stream, (const uint16_t*)x, (const uint16_t*)w, scale, shift, (uint16_t*)y, n, h, wd,
                        c_out, pad, ho, wo, relu, tpb);
     const hipError_t e7 = hipGetLastError();
@@ -472,6 +513,31 @@ int cg_small_cin_conv(const void* x, const void* w, const float* scale, const fl
                      c_in, c_out, k, stride, pad, ho, wo, relu);
   const hipError_t e = hipGetLastError();
   if (e != hipSuccess) return cg::set_error(CG_EHIP, "cg_small_cin_conv: %s", hipGetErrorString(e));
+  return CG_OK;
+}
+
+int cg_conv7x7s2_maxpool(const void* x, const void* w, const float* scale, const float* shift, void* y, int32_t n,
+                         int32_t h, int32_t wd, int32_t c_out, int32_t pad, int32_t relu, void* hip_stream) {
+  if (!x || !w || !y) return cg::set_error(CG_EINVAL, "cg_conv7x7s2_maxpool: x, w and y must not be NULL");
+  if (n < 0 || h <= 0 || wd <= 0) return cg::set_error(CG_EINVAL, "cg_conv7x7s2_maxpool: bad image size");
+  if (c_out <= 0 || c_out % kCb) return cg::set_error(CG_EUNSUPPORTED, "cg_conv7x7s2_maxpool: c_out must be a multiple of 64");
+  if (pad < 0 || pad >= 7) return cg::set_error(CG_EINVAL, "cg_conv7x7s2_maxpool: bad pad");
+  if (h + 2 * pad < 7 || wd + 2 * pad < 7) return cg::set_error(CG_EINVAL, "cg_conv7x7s2_maxpool: kernel larger than the padded input");
+  if ((((uintptr_t)y) | ((uintptr_t)scale) | ((uintptr_t)shift)) & 15)
+    return cg::set_error(CG_EINVAL, "cg_conv7x7s2_maxpool: y, scale and shift must be 16-byte aligned");
+  if (n == 0) return CG_OK;
+  const int ho = (h + 2 * pad - 7) / 2 + 1, wo = (wd + 2 * pad - 7) / 2 + 1;
+  const int pho = (ho - 1) / 2 + 1, pwo = (wo - 1) / 2 + 1;
+  const int tiles_w = (pwo + 6) / 7;
+  const long long rows = (long long)n * ((pho + 6) / 7) * (c_out / kCb);
+  const int tpb = rows >= 512 ? tiles_w : 1;
+  const long long blocks = (long long)n * ((pho + 6) / 7) * ((tiles_w + tpb - 1) / tpb);
+  if (blocks > 0x7fffffffll) return cg::set_error(CG_EUNSUPPORTED, "cg_conv7x7s2_maxpool: too many tiles");
+  hipLaunchKernelGGL(conv7x7s2c3_mfma_kernel<true>, dim3((unsigned)blocks, (unsigned)(c_out / kCb)), dim3(256), 0,
+                     (hipStream_t)hip_stream, (const uint16_t*)x, (const uint16_t*)w, scale, shift, (uint16_t*)y, n, h, wd,
+                     c_out, pad, ho, wo, relu, tpb);
+  const hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return cg::set_error(CG_EHIP, "cg_conv7x7s2_maxpool: %s", hipGetErrorString(e));
   return CG_OK;
 }
 

@@ -101,8 +101,14 @@ class GatedResNet18:
     def _stream(self):
         return torch.cuda.current_stream().cuda_stream
 
-    def _input_layer(self, x):
+    def _input_layer(self, x, keep_conv=True):
+        """The input convolution and the max pooling; keep_conv=False runs them fused (the pooled tensor only)."""
         n = x.shape[0]
+        if not keep_conv:
+            p = torch.empty((n, self.hw_pool, self.hw_pool, 64), dtype=torch.bfloat16, device="cuda")
+            B.cg_conv7x7s2_maxpool(x.data_ptr(), self.w_in.data_ptr(), self.scale_in.data_ptr(), self.shift_in.data_ptr(),
+                                   p.data_ptr(), n, self.size, self.size, 64, 3, True, self._stream())
+            return None, p
         y = torch.empty((n, self.hw_in, self.hw_in, 64), dtype=torch.bfloat16, device="cuda")
         B.cg_small_cin_conv(x.data_ptr(), self.w_in.data_ptr(), self.scale_in.data_ptr(), self.shift_in.data_ptr(),
                             y.data_ptr(), n, self.size, self.size, 3, 64, 7, 2, 3, True, self._stream())
@@ -218,7 +224,7 @@ class GatedResNet18:
         """x: [n, size, size, 3] bf16 device tensor -> logits [n, classes] fp32.  trace: filled with every
         layer's input / residual / output / bitmap (device tensors) when given."""
         n = x.shape[0]
-        stem, cur = self._input_layer(x)
+        stem, cur = self._input_layer(x, keep_conv=trace is not None)
         if trace is not None:
             trace["input"] = dict(x=x, y=stem, pooled=cur)
         block_in = cur

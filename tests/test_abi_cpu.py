@@ -150,6 +150,10 @@ def test_dense_ops_validate_without_a_gpu():
             (lambda: B.cg_small_cin_conv(16, 16, 0, 0, 16, 1, 8, 8, 3, 64, 4, 1, 1, True), B.CG_EUNSUPPORTED),
             (lambda: B.cg_small_cin_conv(16, 16, 0, 0, 16, 1, 2, 2, 3, 64, 7, 2, 1, True), B.CG_EINVAL),
             (lambda: B.cg_small_cin_conv(16, 16, 0, 0, 17, 1, 8, 8, 3, 64, 3, 1, 1, True), B.CG_EINVAL),
+            (lambda: B.cg_conv7x7s2_maxpool(16, 0, 0, 0, 16, 1, 32, 32, 64, 3, True), B.CG_EINVAL),
+            (lambda: B.cg_conv7x7s2_maxpool(16, 16, 0, 0, 16, 1, 32, 32, 48, 3, True), B.CG_EUNSUPPORTED),
+            (lambda: B.cg_conv7x7s2_maxpool(16, 16, 0, 0, 16, 1, 2, 2, 64, 1, True), B.CG_EINVAL),
+            (lambda: B.cg_conv7x7s2_maxpool(16, 16, 0, 0, 16, 1, 32, 32, 64, 7, True), B.CG_EINVAL),
             (lambda: B.cg_pointwise_conv(16, 16, 0, 0, 0, 1, 8, 8, 64, 64, 2, False), B.CG_EINVAL),
             (lambda: B.cg_pointwise_conv(16, 16, 0, 0, 16, 1, 8, 8, 24, 64, 2, False), B.CG_EUNSUPPORTED),
             (lambda: B.cg_pointwise_conv(16, 16, 0, 0, 16, 1, 8, 8, 1024, 64, 2, False), B.CG_EUNSUPPORTED),
@@ -168,5 +172,6 @@ def test_dense_ops_validate_without_a_gpu():
     # zero images: accepted, nothing to do
     B.cg_small_cin_conv(16, 16, 0, 0, 16, 0, 8, 8, 3, 64, 7, 2, 3, True)
     B.cg_pointwise_conv(16, 16, 0, 0, 16, 0, 8, 8, 64, 64, 2, False)
+    B.cg_conv7x7s2_maxpool(16, 16, 0, 0, 16, 0, 32, 32, 64, 3, True)
     B.cg_maxpool3x3s2(16, 16, 0, 8, 8, 8)
     B.cg_avgpool_fc(16, 16, 0, 16, 0, 4, 8, 2)

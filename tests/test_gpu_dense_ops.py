@@ -54,6 +54,36 @@ def test_small_cin_conv(n, h, w, c_in, c_out, k, stride, pad):
         assert (np.abs(got - ref) <= tol).all(), float(np.abs(got - ref).max())
 
 
+@pytest.mark.parametrize("n,h,w,c_out,pad", [(2, 224, 224, 64, 3), (3, 61, 45, 64, 3), (2, 33, 70, 128, 3), (1, 9, 9, 64, 2),
+                                              (70, 64, 64, 64, 3)])
+def test_conv7x7s2_maxpool_fused(n, h, w, c_out, pad):
+    """The fused kernel against the two separate entry points (bit for bit) and against the oracle."""
+    rng = np.random.default_rng(n + h + w)
+    x = _bf16(rng.standard_normal((n, h, w, 3)))
+    wt = _bf16(rng.standard_normal((c_out, 7, 7, 3)) * np.sqrt(2.0 / 147))
+    sc = rng.uniform(0.5, 1.5, c_out).astype(np.float32)
+    sh = (rng.standard_normal(c_out) * 0.3).astype(np.float32)
+    ho, wo = O.out_hw(h, w, 7, 7, 2, pad)
+    pho, pwo = (ho - 1) // 2 + 1, (wo - 1) // 2 + 1
+    xd, wd_, scd, shd = _dev(x), _dev(wt), _dev(sc, torch.float32), _dev(sh, torch.float32)
+    for relu in (True, False):
+        y = torch.empty((n, ho, wo, c_out), dtype=torch.bfloat16, device="cuda")
+        p2 = torch.empty((n, pho, pwo, c_out), dtype=torch.bfloat16, device="cuda")
+        pf = torch.full((n, pho, pwo, c_out), 7.0, dtype=torch.bfloat16, device="cuda")
+        B.cg_small_cin_conv(xd.data_ptr(), wd_.data_ptr(), scd.data_ptr(), shd.data_ptr(), y.data_ptr(), n, h, w, 3, c_out,
+                            7, 2, pad, relu, _stream())
+        B.cg_maxpool3x3s2(y.data_ptr(), p2.data_ptr(), n, ho, wo, c_out, _stream())
+        B.cg_conv7x7s2_maxpool(xd.data_ptr(), wd_.data_ptr(), scd.data_ptr(), shd.data_ptr(), pf.data_ptr(), n, h, w, c_out,
+                               pad, relu, _stream())
+        torch.cuda.synchronize()
+        assert torch.equal(pf, p2)
+        if n <= 3:
+            ref = O.maxpool3x3s2(O.dense_conv(x, wt, stride=2, pad=pad, scale=sc, shift=sh, relu=relu))
+            got = pf.float().cpu().numpy().astype(np.float64)
+            tol = P.ATOL + P.RTOL * np.abs(ref) + P.bf16_ulp(ref)
+            assert (np.abs(got - ref) <= tol).all(), float(np.abs(got - ref).max())
+
+
 @pytest.mark.parametrize("n,h,w,c", [(2, 112, 112, 64), (3, 9, 7, 8), (1, 1, 1, 16), (2, 6, 5, 72)])
 def test_maxpool_bit_exact(n, h, w, c):
     rng = np.random.default_rng(h * 10 + c)

@@ -25,7 +25,9 @@ def test_every_layer_of_a_forward_pass(grouped):
     x = R._t(net.calib_input[:n])
     tr = {}
     logits = net.forward(x, trace=tr)
+    fused = net.forward(x)                  # the pass without a trace fuses the input layer with the pooling
     torch.cuda.synchronize()
+    assert torch.equal(fused, logits)
     f32 = lambda a: np.asarray(a, np.float32).astype(np.float64)
 
     # input layer and pooling
