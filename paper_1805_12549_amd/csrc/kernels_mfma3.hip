@@ -1067,6 +1067,8 @@ Mfma3Plan mfma3_plan(const cg_conv_desc& d) {
         const long long slots = 256ll * ((2 * c.pkb + 2 * gkb + 6 <= 80) ? 2 : 1);
         const int tmax = t;
         double best = 1e30;
+        // (with more than two rounds the workgroups no longer run in step and the larger tile wins)
+        if ((((rows + tmax - 1) / tmax) * g.n_cb + slots - 1) / slots <= 2)
         for (int tt = tmax; 4 * tt >= 3 * tr && tt >= 1; --tt) {     // (three quarters of the pixel slots stay in use)
           const long long wg = ((rows + tt - 1) / tt) * g.n_cb;
           const long long rounds = (wg + slots - 1) / slots;
