@@ -957,7 +957,28 @@ unsigned magic_of3(int d) { return (unsigned)(((1ull << 32) + (unsigned)d - 1) /
 
 }  // namespace
 
+namespace {
+Mfma3Plan plan_with(const cg_conv_desc& d, int max_cps);
+}
+
 Mfma3Plan mfma3_plan(const cg_conv_desc& d) {
+  Mfma3Plan g = plan_with(d, 4);
+  if (g.ok && g.cps == 4 && g.pkb == 48) {
+    // Four-chunk super-stages need the 48 KB patch buffers here (one workgroup per CU).  If the grid has
+    // more workgroups than CUs and two-chunk super-stages fit the 24 KB class, two workgroups per CU
+    // with twice the granules are faster (stride-2 layers: 128->256 at 28x28 -20 %).
+    const int ho = (d.h + 2 * d.pad - 3) / d.stride + 1;
+    const long long wg = (((long long)d.n_max * ho + g.tr - 1) / g.tr) * g.n_cb;
+    if (wg > 256) {
+      const Mfma3Plan h = plan_with(d, 2);
+      if (h.ok && h.pkb == 24) return h;
+    }
+  }
+  return g;
+}
+
+namespace {
+Mfma3Plan plan_with(const cg_conv_desc& d, int max_cps) {
   Mfma3Plan g{};
   g.ok = 0;
   if (d.in_dtype != CG_BF16 && d.in_dtype != CG_I8) return g;
@@ -995,7 +1016,7 @@ Mfma3Plan mfma3_plan(const cg_conv_desc& d) {
     base_k = 2 * d.c_base;
     c_cond = d.c_in;
   }
-  if (base_k % (4 * g.ch) == 0 && c_cond % (4 * g.ch) == 0)
+  if (max_cps >= 4 && base_k % (4 * g.ch) == 0 && c_cond % (4 * g.ch) == 0)
     g.cps = 4;
   else if (base_k % (2 * g.ch) == 0 && c_cond % (2 * g.ch) == 0)
     g.cps = 2;
@@ -1123,6 +1144,7 @@ Mfma3Plan mfma3_plan(const cg_conv_desc& d) {
   }
   return g;
 }
+}  // namespace
 
 hipError_t launch_mfma3_pack(const Mfma3Plan& g, const Params& p, void* wpk_base, void* wpk_cond, hipStream_t s) {
   for (int ph = 0; ph < 2; ++ph) {
