@@ -73,7 +73,7 @@ def main():
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
 
-    variant = {"auto": B.CG_VARIANT_AUTO, "blockskip": B.CG_VARIANT_MFMA, "compact": B.CG_VARIANT_MFMA_COMPACT,
+    variant = {"auto": B.CG_VARIANT_AUTO, "tile": B.CG_VARIANT_TILE,
                "rows": B.CG_VARIANT_MFMA_ROWS}[args.variant]
     shapes = W.imagenet_shapes(n=args.batch)
     if args.layers:

@@ -45,15 +45,16 @@ typedef struct cg_conv cg_conv; /* opaque */
 enum { CG_OK = 0, CG_EINVAL = 1, CG_EUNSUPPORTED = 2, CG_ENOMEM = 3, CG_EHIP = 4 };
 enum { CG_F32 = 0, CG_BF16 = 1, CG_I8 = 2, CG_I32 = 3 };
 enum { CG_EPI_RELU = 1u, CG_EPI_AFFINE = 2u, CG_EPI_RESIDUAL = 4u };
-/* Kernel family.  AUTO picks the row-tiled pixel-compacting matrix-core kernel when the shape
- * allows, else the older pixel-compacting one, else the block-skipping matrix-core kernel, else
- * the plain one-thread-per-activation kernel.  All of them compute the same layer. */
+/* Kernel family.  AUTO picks the row-tiled pixel-compacting matrix-core kernel (3x3 layers whose
+ * channel groups are whole 32-byte runs) when the shape allows, else the large-tile matrix-core
+ * kernel (3x3 and 1x1 layers, fully connected layers as 1x1 layers on a 1x1 image, channel groups of
+ * whole 16-byte runs), else the plain one-thread-per-activation kernel.  All of them compute the
+ * same layer. */
 enum {
   CG_VARIANT_AUTO = 0,
   CG_VARIANT_NAIVE = 1,
-  CG_VARIANT_MFMA = 2,
-  CG_VARIANT_MFMA_COMPACT = 3,
-  CG_VARIANT_MFMA_ROWS = 4
+  CG_VARIANT_MFMA_ROWS = 4,
+  CG_VARIANT_TILE = 5
 };
 
 typedef struct cg_conv_desc {
@@ -118,7 +119,11 @@ typedef struct cg_conv_desc {
    * branch.  y, bitmap and counts then describe the decisions after this gate.  0 = off.
    * Costs a second pass over the base path (the sums must be complete before any conditional work). */
   float tau_c;
-  int32_t reserved0;
+  int32_t tile_hint;         /* 0: the library picks the tile shape.  Otherwise a tuning hint for CG_VARIANT_TILE:
+                                bits 0-3 = 32-pixel fragments per wavefront (4, 2 or 1), bits 4-7 = wavefronts
+                                across the output channels (1 or 2), bits 8-11 = 16-byte channel chunks per K
+                                stage of a 3x3 layer (4, 2 or 1); a zero field is picked by the library.  A
+                                hint the shape cannot take makes create fail with CG_EUNSUPPORTED. */
 
   void* packed;              /* DEVICE, >= cg_conv_packed_bytes(desc), 256-byte aligned, caller-owned;
                                 must outlive the handle; holds repacked weights and per-channel tables */

@@ -46,7 +46,7 @@ if len(_hip_runtimes_mapped()) > 1:
 CG_OK, CG_EINVAL, CG_EUNSUPPORTED, CG_ENOMEM, CG_EHIP = 0, 1, 2, 3, 4
 CG_F32, CG_BF16, CG_I8, CG_I32 = 0, 1, 2, 3
 CG_EPI_RELU, CG_EPI_AFFINE, CG_EPI_RESIDUAL = 1, 2, 4
-CG_VARIANT_AUTO, CG_VARIANT_NAIVE, CG_VARIANT_MFMA, CG_VARIANT_MFMA_COMPACT, CG_VARIANT_MFMA_ROWS = 0, 1, 2, 3, 4
+CG_VARIANT_AUTO, CG_VARIANT_NAIVE, CG_VARIANT_MFMA_ROWS, CG_VARIANT_TILE = 0, 1, 4, 5
 
 EXPORTS = ("cg_conv_packed_bytes", "cg_conv_create", "cg_conv_workspace_bytes", "cg_conv_forward",
            "cg_conv_destroy", "cg_conv_info", "cg_last_error", "cg_small_cin_conv", "cg_conv7x7s2_maxpool", "cg_pointwise_conv",
@@ -71,7 +71,7 @@ class cg_conv_desc(C.Structure):
         ("scale0", _pf), ("shift0", _pf), ("scale1", _pf), ("shift1", _pf),
         ("rq_mult0", _pi), ("rq_mult1", _pi), ("rq_bias", _pi),
         ("rq_shift", C.c_int32), ("rq_res_mult", C.c_int32),
-        ("tau_c", C.c_float), ("reserved0", C.c_int32),
+        ("tau_c", C.c_float), ("tile_hint", C.c_int32),
         ("packed", C.c_void_p), ("packed_bytes", C.c_size_t),
     ]
 
@@ -220,7 +220,7 @@ class GatedConv:
                  gate_mean=None, gate_var=None, delta=None, delta_hi=None, gate_eps=0.0, gate_thr_i32=None,
                  scale0=None, shift0=None, scale1=None, shift1=None,
                  rq_mult0=None, rq_mult1=None, rq_bias=None, rq_shift=0, rq_res_mult=0,
-                 x_pixel_stride=0, groups=0, shuffle=False, tau_c=0.0, stream=None):
+                 x_pixel_stride=0, groups=0, shuffle=False, tau_c=0.0, tile_hint=0, stream=None):
         import torch
         self._torch = torch
         self.handle = None
@@ -232,6 +232,7 @@ class GatedConv:
         d.x_pixel_stride = x_pixel_stride
         d.groups, d.shuffle = int(groups), int(bool(shuffle))
         d.tau_c = float(tau_c)
+        d.tile_hint = int(tile_hint)
         self._keep = [w_base, w_cond]
         d.w_base = w_base.data_ptr()
         d.w_cond = w_cond.data_ptr() if (w_cond is not None and w_cond.numel()) else None

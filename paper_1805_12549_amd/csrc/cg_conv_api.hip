@@ -71,9 +71,8 @@ struct cg_conv {
   cg_conv_desc d;           // copy of the descriptor (host pointers are dead after create)
   int ho, wo, c_cond;
   int variant;              // resolved CG_VARIANT_*
-  cg::MfmaPlan plan;
-  cg::Mfma2Plan plan2;
   cg::Mfma3Plan plan3;
+  cg::TilePlan plan4;
   Layout lay;
   std::vector<uint32_t> staging;  // host image of the tables; kept alive for the async copy
 };
@@ -103,9 +102,11 @@ int validate(const cg_conv_desc* d, int* ho, int* wo) {
   if (d->shuffle != 0 && d->shuffle != 1) return fail(CG_EINVAL, "shuffle must be 0 or 1");
   if (d->shuffle && d->groups <= 1) return fail(CG_EINVAL, "shuffle needs channel grouping (groups > 1)");
   if (!(d->tau_c >= 0.0f) || std::isinf(d->tau_c)) return fail(CG_EINVAL, "tau_c must be finite and >= 0");
+  if (d->tile_hint < 0 || d->tile_hint >= (1 << 12)) return fail(CG_EINVAL, "tile_hint has bits outside its three fields");
   if (d->in_dtype != CG_F32 && d->in_dtype != CG_BF16 && d->in_dtype != CG_I8)
     return fail(CG_EINVAL, "in_dtype must be CG_F32, CG_BF16 or CG_I8");
   if (d->in_dtype == CG_I8) {
+    if (d->delta_hi) return fail(CG_EUNSUPPORTED, "the upper gate threshold (delta_hi) exists for float inputs only");
     if (d->out_dtype != CG_I32 && d->out_dtype != CG_I8)
       return fail(CG_EINVAL, "int8 inputs need out_dtype CG_I32 or CG_I8");
     if (d->rq_shift < 0 || d->rq_shift > 31) return fail(CG_EINVAL, "rq_shift must lie in [0, 31]");
@@ -113,8 +114,8 @@ int validate(const cg_conv_desc* d, int* ho, int* wo) {
     return fail(CG_EINVAL, "float inputs need out_dtype CG_F32 or CG_BF16");
   }
   if (d->epilogue & ~(CG_EPI_RELU | CG_EPI_AFFINE | CG_EPI_RESIDUAL)) return fail(CG_EINVAL, "unknown epilogue flag");
-  if (d->variant != CG_VARIANT_AUTO && d->variant != CG_VARIANT_NAIVE && d->variant != CG_VARIANT_MFMA &&
-      d->variant != CG_VARIANT_MFMA_COMPACT && d->variant != CG_VARIANT_MFMA_ROWS)
+  if (d->variant != CG_VARIANT_AUTO && d->variant != CG_VARIANT_NAIVE && d->variant != CG_VARIANT_MFMA_ROWS &&
+      d->variant != CG_VARIANT_TILE)
     return fail(CG_EINVAL, "unknown variant %d", d->variant);
   if (d->x_pixel_stride != 0 && d->x_pixel_stride < d->c_in)
     return fail(CG_EINVAL, "x_pixel_stride must be 0 or >= c_in");
@@ -169,38 +170,38 @@ Layout make_layout(const cg_conv_desc& d, size_t wpk_base_bytes, size_t wpk_cond
 }
 
 struct Plans {
-  cg::MfmaPlan v1;
-  cg::Mfma2Plan v2;
   cg::Mfma3Plan v3;
+  cg::TilePlan v4;
   int variant;
   size_t wpk_base_bytes, wpk_cond_bytes;
 };
 
+// compute units of the current device (256 where no device answers: the plan is then the MI355X one)
+int cu_count() {
+  static int cached = 0;
+  if (cached > 0) return cached;
+  int dev = 0, n = 0;
+  if (hipGetDevice(&dev) == hipSuccess &&
+      hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0) {
+    cached = n;
+    return n;
+  }
+  (void)hipGetLastError();
+  return 256;
+}
+
 int resolve_variant(const cg_conv_desc& d, Plans* pl) {
-  pl->v1 = cg::mfma_plan(d);
-  pl->v2 = cg::mfma2_plan(d);
-  pl->v3 = cg::mfma3_plan(d);
-  if (d.variant == CG_VARIANT_MFMA && !pl->v1.ok)
-    return fail(CG_EUNSUPPORTED, "the block-skipping matrix-core kernel does not cover this shape/dtype");
-  if (d.variant == CG_VARIANT_MFMA_COMPACT && !pl->v2.ok)
-    return fail(CG_EUNSUPPORTED, "the pixel-compacting matrix-core kernel does not cover this shape/dtype");
+  pl->v4 = cg::tile_plan(d, cu_count());
+  pl->v3 = cg::mfma3_plan(d, cu_count());
+  if (d.variant == CG_VARIANT_TILE && !pl->v4.ok)
+    return fail(CG_EUNSUPPORTED, "the large-tile matrix-core kernel does not cover this shape/dtype");
   if (d.variant == CG_VARIANT_MFMA_ROWS && !pl->v3.ok)
     return fail(CG_EUNSUPPORTED, "the row-tiled matrix-core kernel does not cover this shape/dtype");
   int v = d.variant;
-  if (v == CG_VARIANT_AUTO)
-    v = pl->v3.ok   ? CG_VARIANT_MFMA_ROWS
-        : pl->v2.ok ? CG_VARIANT_MFMA_COMPACT
-        : pl->v1.ok ? CG_VARIANT_MFMA
-                    : CG_VARIANT_NAIVE;
+  if (v == CG_VARIANT_AUTO) v = pl->v3.ok ? CG_VARIANT_MFMA_ROWS : pl->v4.ok ? CG_VARIANT_TILE : CG_VARIANT_NAIVE;
   pl->variant = v;
-  pl->wpk_base_bytes = v == CG_VARIANT_MFMA_ROWS      ? pl->v3.wpk_base_bytes
-                       : v == CG_VARIANT_MFMA_COMPACT ? pl->v2.wpk_base_bytes
-                       : v == CG_VARIANT_MFMA         ? pl->v1.wpk_base_bytes
-                                                      : 0;
-  pl->wpk_cond_bytes = v == CG_VARIANT_MFMA_ROWS      ? pl->v3.wpk_cond_bytes
-                       : v == CG_VARIANT_MFMA_COMPACT ? pl->v2.wpk_cond_bytes
-                       : v == CG_VARIANT_MFMA         ? pl->v1.wpk_cond_bytes
-                                                      : 0;
+  pl->wpk_base_bytes = v == CG_VARIANT_TILE ? pl->v4.wpk_base_bytes : v == CG_VARIANT_MFMA_ROWS ? pl->v3.wpk_base_bytes : 0;
+  pl->wpk_cond_bytes = v == CG_VARIANT_TILE ? pl->v4.wpk_cond_bytes : v == CG_VARIANT_MFMA_ROWS ? pl->v3.wpk_cond_bytes : 0;
   return CG_OK;
 }
 
@@ -221,10 +222,6 @@ size_t cg_conv_packed_bytes(const cg_conv_desc* desc) {
   if (validate(desc, &ho, &wo) != CG_OK) return 0;
   Plans pl;
   if (resolve_variant(*desc, &pl) != CG_OK) return 0;
-  if (getenv("CG_DEBUG") && pl.v3.ok)
-    fprintf(stderr, "[cg_conv] rows plan: nwv=%d nf=%d bm=%d n_cb=%d tr=%d pitch=%d pr=%d cps=%d ni=%d pkb=%d stages=%d,%d\n",
-            pl.v3.nwv, pl.v3.nf, pl.v3.bm, pl.v3.n_cb, pl.v3.tr, 1 << pl.v3.logp, pl.v3.pr, pl.v3.cps, pl.v3.ni, pl.v3.pkb,
-            pl.v3.stages[0], pl.v3.stages[1]);
   return make_layout(*desc, pl.wpk_base_bytes, pl.wpk_cond_bytes).total;
 }
 
@@ -239,28 +236,8 @@ int cg_conv_create(cg_conv** out, const cg_conv_desc* desc, void* hip_stream) {
   rc = resolve_variant(d, &pl);
   if (rc != CG_OK) return rc;
   const int variant = pl.variant;
-  const cg::MfmaPlan& plan = pl.v1;
-  const cg::Mfma2Plan& plan2 = pl.v2;
   const cg::Mfma3Plan& plan3 = pl.v3;
   const Layout lay = make_layout(d, pl.wpk_base_bytes, pl.wpk_cond_bytes);
-  if (getenv("CG_DEBUG"))
-    fprintf(stderr,
-            "[cg_conv] variant=%d plan.ok=%d bn=%d n_cb=%d tr=%d ti=%d tiles/img=%d patch=%dx%d npix=%d bm=%d ng=%d "
-            "cbq=%d,%d stages=%d,%d steps=%d,%d ps=%d,%d lds=%d packed=%zu\n",
-            variant, plan.ok, plan.bn, plan.n_cb, plan.tr, plan.ti, plan.tiles_per_img, plan.pr, plan.pwid, plan.npix,
-            plan.bm_valid, plan.ng, plan.cbq[0], plan.cbq[1], plan.stages[0], plan.stages[1], plan.tsteps[0],
-            plan.tsteps[1], plan.ps[0], plan.ps[1], plan.lds_total, lay.total);
-  if (getenv("CG_DEBUG") && plan2.ok)
-    fprintf(stderr,
-            "[cg_conv] compact plan: ngw=%d bm=%d n_cb=%d tr=%d patch=%dx%d npix=%d bm_valid=%d ng=%d max_imgs=%d cbq=%d "
-            "stages=%d,%d steps=%d kp=%d stage_bytes=%d lds=%d\n",
-            plan2.ngw, plan2.bm, plan2.n_cb, plan2.tr, plan2.pr_max, plan2.pw, plan2.npix, plan2.bm_valid, plan2.ng,
-            plan2.max_imgs, plan2.cbq, plan2.stages[0], plan2.stages[1], plan2.tsteps, plan2.kp, plan2.stage_bytes,
-            plan2.lds_total);
-  if (getenv("CG_DEBUG") && plan3.ok)
-    fprintf(stderr, "[cg_conv] rows plan: nwv=%d nf=%d bm=%d n_cb=%d tr=%d pitch=%d pr=%d cps=%d ni=%d pkb=%d stages=%d,%d\n",
-            plan3.nwv, plan3.nf, plan3.bm, plan3.n_cb, plan3.tr, 1 << plan3.logp, plan3.pr, plan3.cps, plan3.ni, plan3.pkb,
-            plan3.stages[0], plan3.stages[1]);
   if (!d.packed) return fail(CG_EINVAL, "packed is NULL");
   if (((uintptr_t)d.packed & 255) != 0) return fail(CG_EINVAL, "packed must be 256-byte aligned");
   if (d.packed_bytes < lay.total)
@@ -274,9 +251,8 @@ int cg_conv_create(cg_conv** out, const cg_conv_desc* desc, void* hip_stream) {
   h->wo = wo;
   h->c_cond = d.c_in - d.c_base;
   h->variant = variant;
-  h->plan = plan;
-  h->plan2 = plan2;
   h->plan3 = plan3;
+  h->plan4 = pl.v4;
   h->lay = lay;
 
   // Host image of the per-channel tables.
@@ -344,10 +320,8 @@ int cg_conv_create(cg_conv** out, const cg_conv_desc* desc, void* hip_stream) {
     p.cpg = d.c_out / p.groups;
     p.w_base = pk + lay.w_base_off;
     p.w_cond = pk + lay.w_cond_off;
-    if (variant == CG_VARIANT_MFMA)
-      e = cg::launch_mfma_pack(plan, p, pk + lay.wpk_base_off, pk + lay.wpk_cond_off, s);
-    else if (variant == CG_VARIANT_MFMA_COMPACT)
-      e = cg::launch_mfma2_pack(plan2, p, pk + lay.wpk_base_off, pk + lay.wpk_cond_off, s);
+    if (variant == CG_VARIANT_TILE)
+      e = cg::launch_tile_pack(pl.v4, p, pk + lay.wpk_base_off, pk + lay.wpk_cond_off, s);
     else
       e = cg::launch_mfma3_pack(plan3, p, pk + lay.wpk_base_off, pk + lay.wpk_cond_off, s);
   }
@@ -373,7 +347,7 @@ WsLayout ws_layout(const cg_conv* h, int32_t n) {
   WsLayout w{};
   const size_t words = (size_t)(h->d.c_out + 31) / 32;
   const bool chan_gate = h->c_cond > 0 && h->d.tau_c > 0.0f;
-  if (h->variant == CG_VARIANT_MFMA_ROWS && h->c_cond > 0)
+  if ((h->variant == CG_VARIANT_MFMA_ROWS || h->variant == CG_VARIANT_TILE) && h->c_cond > 0)
     w.bitmap_bytes = align256((size_t)n * h->ho * h->wo * words * 4);
   if (chan_gate) {
     w.counts_bytes = align256((2 + (size_t)n * h->d.c_out) * 4);
@@ -399,8 +373,30 @@ int cg_conv_info(const cg_conv* h, int32_t* ho, int32_t* wo) {
   return h->variant;
 }
 
+}  // extern "C"
+
+namespace {
+
+int forward_impl(cg_conv* h, int32_t n, const void* x, const void* residual, void* y, uint32_t* bitmap,
+                 uint32_t* counts, void* workspace, size_t workspace_bytes, void* hip_stream);
+
+}  // namespace
+
+extern "C" {
+
 int cg_conv_forward(cg_conv* h, int32_t n, const void* x, const void* residual, void* y, uint32_t* bitmap,
                     uint32_t* counts, void* workspace, size_t workspace_bytes, void* hip_stream) {
+  return forward_impl(h, n, x, residual, y, bitmap, counts, workspace, workspace_bytes, hip_stream);
+}
+
+void cg_conv_destroy(cg_conv* h) { delete h; }
+
+}  // extern "C"
+
+namespace {
+
+int forward_impl(cg_conv* h, int32_t n, const void* x, const void* residual, void* y, uint32_t* bitmap,
+                 uint32_t* counts, void* workspace, size_t workspace_bytes, void* hip_stream) {
   if (!h) return fail(CG_EINVAL, "handle is NULL");
   if (n < 0 || n > h->d.n_max) return fail(CG_EINVAL, "n = %d is outside [0, n_max = %d]", n, h->d.n_max);
   if (n == 0) return CG_OK;
@@ -458,11 +454,33 @@ int cg_conv_forward(cg_conv* h, int32_t n, const void* x, const void* residual, 
   p.bias = (const int32_t*)(pk + 4 * ts);
   p.w_base = pk + l.w_base_off;
   p.w_cond = pk + l.w_cond_off;
+  p.table_stride = ts;
+  p.zeros = pk + 7 * ts;       // the last table is never written: zeros
   p.x = x;
   p.residual = residual;
   p.y = y;
   p.bitmap = bitmap;
   p.counts = counts;
+
+  // The launch shape follows the batch of this call: a smaller batch than n_max is planned afresh
+  // and the new plan is used if it reads the prepacked weights the same way.
+  cg::Mfma3Plan plan3 = h->plan3;
+  cg::TilePlan plan4 = h->plan4;
+  if (n != d.n_max && h->variant != CG_VARIANT_NAIVE) {
+    cg_conv_desc dn = d;
+    dn.n_max = n;
+    if (h->variant == CG_VARIANT_MFMA_ROWS) {
+      const cg::Mfma3Plan q = cg::mfma3_plan(dn, cu_count());
+      if (q.ok && q.cps == plan3.cps && q.grp_mode == plan3.grp_mode && q.gsp == plan3.gsp &&
+          q.stages[0] == plan3.stages[0] && q.stages[1] == plan3.stages[1])
+        plan3 = q;
+    } else {
+      const cg::TilePlan q = cg::tile_plan(dn, cu_count());
+      if (q.ok && q.taps == plan4.taps && q.cps == plan4.cps && q.wn == plan4.wn && q.grp_mode == plan4.grp_mode &&
+          q.gsp == plan4.gsp && q.stages[0] == plan4.stages[0] && q.stages[1] == plan4.stages[1])
+        plan4 = q;
+    }
+  }
 
   hipStream_t s = (hipStream_t)hip_stream;
   hipError_t e = hipSuccess;
@@ -481,9 +499,10 @@ int cg_conv_forward(cg_conv* h, int32_t n, const void* x, const void* residual, 
     q.y = nullptr;
     q.counts = nullptr;
     q.bitmap = nullptr;
-    if (h->variant == CG_VARIANT_MFMA_ROWS) {
+    if (h->variant == CG_VARIANT_MFMA_ROWS || h->variant == CG_VARIANT_TILE) {
       q.bitmap = (uint32_t*)(ws + wl.bitmap_off);
-      e = cg::launch_mfma3(h->plan3, q, pk + l.wpk_base_off, pk + l.wpk_cond_off, s);
+      e = h->variant == CG_VARIANT_TILE ? cg::launch_tile(plan4, q, pk + l.wpk_base_off, pk + l.wpk_cond_off, s)
+                                        : cg::launch_mfma3(plan3, q, pk + l.wpk_base_off, pk + l.wpk_cond_off, s);
       if (e == hipSuccess) e = cg::launch_bitmap_chan_mask(q, q.bitmap, need_u, mask, s);
     } else {
       e = cg::launch_zero_u32(pre_counts, 2 + (size_t)n * d.c_out, s);
@@ -494,27 +513,22 @@ int cg_conv_forward(cg_conv* h, int32_t n, const void* x, const void* residual, 
     p.chan_mask = mask;
   }
   if (e == hipSuccess && counts) e = cg::launch_zero_u32(counts, 2 + (size_t)n * d.c_out, s);
-  if (e == hipSuccess && h->variant == CG_VARIANT_MFMA_ROWS) {
+  if (e == hipSuccess && (h->variant == CG_VARIANT_MFMA_ROWS || h->variant == CG_VARIANT_TILE)) {
     const size_t bm_words = (size_t)p.m_total * p.words;
     if (!p.gated) {
       if (bitmap) e = cg::launch_zero_u32(bitmap, bm_words, s);   // a dense layer has no decisions
     } else if (counts && !bitmap) {
       p.bitmap = (uint32_t*)(ws + wl.bitmap_off);   // free again once the mask exists
     }
-    if (e == hipSuccess) e = cg::launch_mfma3(h->plan3, p, pk + l.wpk_base_off, pk + l.wpk_cond_off, s);
+    if (e == hipSuccess)
+      e = h->variant == CG_VARIANT_TILE ? cg::launch_tile(plan4, p, pk + l.wpk_base_off, pk + l.wpk_cond_off, s)
+                                        : cg::launch_mfma3(plan3, p, pk + l.wpk_base_off, pk + l.wpk_cond_off, s);
     if (e == hipSuccess && counts && p.gated) e = cg::launch_bitmap_counts(p, p.bitmap, s);
   } else if (e == hipSuccess) {
-    if (h->variant == CG_VARIANT_MFMA_COMPACT)
-      e = cg::launch_mfma2(h->plan2, p, pk + l.wpk_base_off, pk + l.wpk_cond_off, s);
-    else if (h->variant == CG_VARIANT_MFMA)
-      e = cg::launch_mfma(h->plan, p, pk + l.wpk_base_off, pk + l.wpk_cond_off, s);
-    else
-      e = cg::launch_naive(p, s);
+    e = cg::launch_naive(p, s);
   }
   if (e != hipSuccess) return fail(CG_EHIP, "cg_conv_forward: %s", hipGetErrorString(e));
   return CG_OK;
 }
 
-void cg_conv_destroy(cg_conv* h) { delete h; }
-
-}  // extern "C"
+}  // namespace

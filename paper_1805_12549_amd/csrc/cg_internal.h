@@ -39,6 +39,8 @@ struct Params {
   // weights in caller layout [c_out][kh][kw][c], copied into `packed`
   const void* w_base;
   const void* w_cond;
+  size_t table_stride;     // bytes between the per-channel tables of `packed`; thr_f is table 0
+  const void* zeros;       // at least 256 bytes of zeros (source of the padding in the LDS-direct loads)
 
   // call arguments
   const void* x;
@@ -48,72 +50,54 @@ struct Params {
   uint32_t* counts;
 };
 
-// Geometry of the matrix-core kernels for one layer (host-computed, passed by value).
-//
-// A workgroup owns a tile of up to 128 output pixels (`ti` whole images or `tr` output
-// rows of one image) times BN output channels.  The input patch those pixels read is
-// staged in LDS once per K stage, `cbq` 16-byte channel chunks per pixel at a time,
-// together with the matching slice of prepacked weights.  Phase 0 is the base path
-// (channels [0,c_base)), phase 1 the conditional path.
-struct MfmaPlan {
-  int ok;                  // 0: shape not covered by the matrix-core kernels
-  int elem_bytes;          // 2 (bf16) or 1 (int8)
-  int ch;                  // channels per 16-byte chunk: 8 (bf16) or 16 (int8)
-  int bn;                  // output channels per workgroup (64 or 128)
-  int n_cb;                // c_out / bn
-  int tr, ti;              // output rows per tile / images per tile (ti > 1 only with tr == ho)
-  int tiles_per_img;       // ceil(ho / tr) when ti == 1
-  int pr, pwid, npix;      // patch rows, patch width, patch pixels = ti*pr*pwid
-  int bm_valid;            // ti*tr*wo output pixels per full tile (<= 128)
-  int ng;                  // 16-pixel row groups per tile = ceil(bm_valid / 16)
-  int taps;                // kh*kw
-  int cbq[2];              // 16-byte chunks per pixel per stage
-  int stages[2];           // K stages per phase (0 for an absent phase)
-  int tsteps[2];           // MFMA K steps per stage = ceil(taps*cbq / 4)
-  int ps[2];               // LDS bytes per patch pixel (odd multiple of 16: conflict-free reads)
-  // LDS byte offsets
-  int lds_aoff, lds_gidx, lds_outpp, lds_outm, lds_colcnt, lds_dbits, lds_stage, lds_w[2], lds_total;
-  size_t wpk_stage_bytes[2];  // bytes of one (column block, stage) slice of prepacked weights
+// Geometry of the large-tile matrix-core kernel (kernels_tile.hip): four wavefronts per workgroup,
+// one workgroup per compute unit, a wavefront multiplies `fp` 32-pixel fragments by 64 channels.
+// K is walked in stages of `cps` 16-byte channel chunks per pixel times all taps.
+struct TilePlan {
+  int ok;
+  int elem_bytes, ch;      // bytes per element; channels per 16-byte chunk
+  int taps;                // 9 (3x3) or 1 (1x1)
+  int cps;                 // chunks per pixel per stage
+  int fp;                  // 32-pixel fragments per wavefront: 4, 2 or 1
+  int wn;                  // wavefronts across the channels: 1 (64-channel block) or 2 (128)
+  int bn, n_cb;            // channels per block, number of blocks
+  int flat, vw;            // flat: a 1x1 stride-1 layer walked as one image of rows of vw pixels
+  int tr;                  // output rows per tile
+  int hp;                  // h + 2*pad of the geometry walked (for n_max)
+  int logp;                // log2 of the patch row pitch in pixel slots
+  int pr;                  // patch rows, maximum over tiles
+  int n16;                 // 16-byte positions of a stage's patch = pr * pitch * cps
+  int xcd_cb;              // 1: blocks of one channel block share an XCD; 0: blocks of one tile do
+  int grp_mode, gsp;       // channel grouping, as in Mfma3Plan
+  int stages[2];           // stages of the base / conditional phase
+  int nb;                  // stage buffers in LDS (the loads run nb - 1 stages ahead)
+  size_t lds_bytes;        // LDS of the kernel instantiation
+  size_t wpk_stage_bytes;  // bytes of one (channel block, stage) slab of prepacked weights
   size_t wpk_base_bytes, wpk_cond_bytes;
 };
 
-MfmaPlan mfma_plan(const cg_conv_desc& d);
-
-// Geometry of the pixel-compacting matrix-core kernel.
-//
-// Output rows of the whole batch are numbered R = img*Ho + ho.  A workgroup owns `tr`
-// consecutive global rows (<= bm pixels, they may straddle images) x 64 output channels.
-// Input rows live in a "stacked padded" space, row = img*(H+2*pad) + hi + pad, in which the
-// rows a tile reads form one contiguous range even across an image boundary.
-struct Mfma2Plan {
-  int ok;
-  int elem_bytes, ch;      // bytes per element; channels per 16-byte chunk
-  int ngw;                 // 16-pixel row groups per wavefront in the base phase (1 or 2)
-  int bm;                  // ngw*16*wavefronts: pixels per tile, padded
-  int n_cb;                // c_out / 64
-  int tr;                  // global output rows per tile
-  int hp;                  // h + 2*pad
-  unsigned magic_hp, magic_ho, magic_wo;   // ceil(2^32 / d): exact division of 16-bit values by hp, ho, wo
-  int pr_max, pw, npix;    // patch rows (max over tiles), patch width, pr_max*pw
-  int bm_valid;            // tr*wo
-  int ng;                  // ceil(bm_valid/16)
-  int max_imgs;            // images one tile can touch
-  int cbq;                 // 16-byte channel chunks per pixel per K stage: 1, 2 or 4
-  int stages[2];           // K stages of the base / conditional phase
-  int tsteps;              // MFMA K steps per stage = ceil(9*cbq/4)
-  int kp;                  // patch chunk slots per thread per stage
-  int pln, nps;            // bytes / 16-byte slots per chunk plane of the LDS patch (npix pixels + a zero pixel, padded)
-  unsigned magic_nps;
-  int patch_bytes, w_bytes, stage_bytes;
-  int lds_goff, lds_outpp, lds_outm, lds_flag, lds_clist, lds_rank, lds_dbits, lds_colcnt, lds_zero, lds_misc,
-      lds_stage, lds_total;
-  size_t wpk_stage_bytes, wpk_base_bytes, wpk_cond_bytes;
+// the image geometry the kernel walks for one call (the layer's own, or the flat renumbering)
+struct TileGeo {
+  int n, h, w, ho, wo, stride, pad, hp;
+  unsigned magic_hp, magic_ho, magic_wo;
+  long long m_valid;       // output pixels
+  long long in_valid;      // input pixels
+  int xps;                 // bytes between input pixels
 };
 
-Mfma2Plan mfma2_plan(const cg_conv_desc& d);
-hipError_t launch_mfma2_pack(const Mfma2Plan& plan, const Params& p, void* wpk_base, void* wpk_cond, hipStream_t s);
-hipError_t launch_mfma2(const Mfma2Plan& plan, const Params& p, const void* wpk_base, const void* wpk_cond,
-                        hipStream_t s);
+TilePlan tile_plan(const cg_conv_desc& d, int n_cu);
+hipError_t launch_tile_pack(const TilePlan& plan, const Params& p, void* wpk_base, void* wpk_cond, hipStream_t s);
+hipError_t launch_tile(const TilePlan& plan, const Params& p, const void* wpk_base, const void* wpk_cond,
+                       hipStream_t s);
+// one translation unit per (dtype, kernel size): the instantiations of the tile kernel
+hipError_t launch_tile_bf16_k3(const TilePlan& g, const TileGeo& q, const Params& p, const void* w0, const void* w1,
+                               hipStream_t s);
+hipError_t launch_tile_bf16_k1(const TilePlan& g, const TileGeo& q, const Params& p, const void* w0, const void* w1,
+                               hipStream_t s);
+hipError_t launch_tile_i8_k3(const TilePlan& g, const TileGeo& q, const Params& p, const void* w0, const void* w1,
+                             hipStream_t s);
+hipError_t launch_tile_i8_k1(const TilePlan& g, const TileGeo& q, const Params& p, const void* w0, const void* w1,
+                             hipStream_t s);
 
 // Geometry of the row-tiled matrix-core kernel (32x32 MFMA blocks, transposed product).
 //
@@ -148,7 +132,7 @@ struct Mfma3Plan {
   size_t wpk_base_bytes, wpk_cond_bytes;
 };
 
-Mfma3Plan mfma3_plan(const cg_conv_desc& d);
+Mfma3Plan mfma3_plan(const cg_conv_desc& d, int n_cu);
 hipError_t launch_mfma3_pack(const Mfma3Plan& plan, const Params& p, void* wpk_base, void* wpk_cond, hipStream_t s);
 hipError_t launch_mfma3(const Mfma3Plan& plan, const Params& p, const void* wpk_base, const void* wpk_cond,
                         hipStream_t s);
@@ -165,8 +149,5 @@ hipError_t launch_chan_mask(const uint32_t* counts, int n, int c_out, int words,
 // launchers (return hipError_t from the last launch)
 hipError_t launch_naive(const Params& p, hipStream_t s);
 hipError_t launch_zero_u32(uint32_t* ptr, size_t words, hipStream_t s);
-hipError_t launch_mfma_pack(const MfmaPlan& plan, const Params& p, void* wpk_base, void* wpk_cond, hipStream_t s);
-hipError_t launch_mfma(const MfmaPlan& plan, const Params& p, const void* wpk_base, const void* wpk_cond,
-                       hipStream_t s);
 
 }  // namespace cg

@@ -153,9 +153,4 @@ __device__ __forceinline__ void finish_store8(const Params& p, i32x4 s0, i32x4 s
   }
 }
 
-// weight prepack shared by both matrix-core kernels (defined in kernels_mfma.hip):
-// [c_out][taps][c] -> [column block][stage][e = 4*step + lane group][bn][16 bytes]
-hipError_t launch_pack_weights(const void* w, void* out, int c_out, int taps, int c_phase, int eb, int ch, int bn,
-                               int cbq, int stages, int tsteps, hipStream_t s);
-
 }  // namespace cg

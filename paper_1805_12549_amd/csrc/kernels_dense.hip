@@ -432,7 +432,10 @@ __global__ __launch_bounds__(1024) void avgpool_fc_kernel(const uint16_t* __rest
     const int cpad = (c + 63) & ~63;
     const int groups = (int)blockDim.x / cpad > 0 ? (int)blockDim.x / cpad : 1;
     for (int ch0 = 0; ch0 < c; ch0 += groups > 1 ? c : (int)blockDim.x) {
-      const int ch = ch0 + (int)threadIdx.x % cpad, g = (int)threadIdx.x / cpad;
+      // a single group strides over the channels by thread index (threads past cpad would otherwise
+      // alias the channels of the first ones); several groups split the positions
+      const int ch = groups == 1 ? ch0 + (int)threadIdx.x : (int)threadIdx.x % cpad;
+      const int g = groups == 1 ? 0 : (int)threadIdx.x / cpad;
       float s = 0.0f;
       if (ch < c && g < groups)
         for (int p = g; p < hw; p += groups) s += bf16_to_float(x[((long long)img * hw + p) * c + ch]);

@@ -79,7 +79,8 @@ __device__ __forceinline__ int as_bits(int v) { return v; }
 __device__ __forceinline__ void from_bits(int b, float& f) { f = __int_as_float(b); }
 __device__ __forceinline__ void from_bits(int b, int& v) { v = b; }
 
-__device__ __forceinline__ int fdiv3(int x, unsigned magic) { return (int)__umulhi((unsigned)x, magic); }
+// exact x / d for x, d < 65536 with magic = ceil(2^32 / d); magic 0 stands for d = 1 (2^32 does not fit)
+__device__ __forceinline__ int fdiv3(int x, unsigned magic) { return magic ? (int)__umulhi((unsigned)x, magic) : x; }
 
 __device__ __forceinline__ void lds_direct16(const char* gsrc, char* ldst) {
   // each active lane copies 16 bytes from its own global address to ldst + lane*16
@@ -953,24 +954,24 @@ hipError_t launch_rows_dtype(const Mfma3Plan& g, const Params& p, const void* w0
   return launch_rows_cps<Tr, 1, 2>(g, p, w0, w1, s);
 }
 
-unsigned magic_of3(int d) { return (unsigned)(((1ull << 32) + (unsigned)d - 1) / (unsigned)d); }
+unsigned magic_of3(int d) { return d == 1 ? 0u : (unsigned)(((1ull << 32) + (unsigned)d - 1) / (unsigned)d); }
 
 }  // namespace
 
 namespace {
-Mfma3Plan plan_with(const cg_conv_desc& d, int max_cps);
+Mfma3Plan plan_with(const cg_conv_desc& d, int max_cps, int n_cu);
 }
 
-Mfma3Plan mfma3_plan(const cg_conv_desc& d) {
-  Mfma3Plan g = plan_with(d, 4);
+Mfma3Plan mfma3_plan(const cg_conv_desc& d, int n_cu) {
+  Mfma3Plan g = plan_with(d, 4, n_cu);
   if (g.ok && g.cps == 4 && g.pkb == 48) {
     // Four-chunk super-stages need the 48 KB patch buffers here (one workgroup per CU).  If the grid has
     // more workgroups than CUs and two-chunk super-stages fit the 24 KB class, two workgroups per CU
     // with twice the granules are faster (stride-2 layers: 128->256 at 28x28 -20 %).
     const int ho = (d.h + 2 * d.pad - 3) / d.stride + 1;
     const long long wg = (((long long)d.n_max * ho + g.tr - 1) / g.tr) * g.n_cb;
-    if (wg > 256) {
-      const Mfma3Plan h = plan_with(d, 2);
+    if (wg > n_cu) {
+      const Mfma3Plan h = plan_with(d, 2, n_cu);
       if (h.ok && h.pkb == 24) return h;
     }
   }
@@ -978,7 +979,7 @@ Mfma3Plan mfma3_plan(const cg_conv_desc& d) {
 }
 
 namespace {
-Mfma3Plan plan_with(const cg_conv_desc& d, int max_cps) {
+Mfma3Plan plan_with(const cg_conv_desc& d, int max_cps, int n_cu) {
   Mfma3Plan g{};
   g.ok = 0;
   if (d.in_dtype != CG_BF16 && d.in_dtype != CG_I8) return g;
@@ -1078,14 +1079,14 @@ Mfma3Plan plan_with(const cg_conv_desc& d, int max_cps) {
       int t = tr;
       while (t >= 1 && (long long)patch_rows(t) * P * sb > c.pkb * 1024) --t;
       if (t < 1 || 4 * t < 3 * tr) continue;
-      if (nf == 2 && ((rows + t - 1) / t) * g.n_cb < 256) continue;   // the large tile only when it still fills the CUs
+      if (nf == 2 && ((rows + t - 1) / t) * g.n_cb < n_cu) continue;   // the large tile only when it still fills the CUs
       {
         // Balance the grid: with fewer rows per tile the tiles may come out as a whole number of
-        // rounds over the CUs (256 CUs, two workgroups each where LDS allows), which shortens the
+        // rounds over the CUs (two workgroups each where LDS allows), which shortens the
         // longest CU's share.  Cost of a choice = rounds x (rows per tile + a per-round share for
         // prologue, gate and epilogue); ties keep the larger tile.
         const int gkb = 3 * g.cps;
-        const long long slots = 256ll * ((2 * c.pkb + 2 * gkb + 6 <= 80) ? 2 : 1);
+        const long long slots = (long long)n_cu * ((2 * c.pkb + 2 * gkb + 6 <= 80) ? 2 : 1);
         const int tmax = t;
         double best = 1e30;
         // (with more than two rounds the workgroups no longer run in step and the larger tile wins)
@@ -1106,7 +1107,7 @@ Mfma3Plan plan_with(const cg_conv_desc& d, int max_cps) {
       g.nf = nf;
       g.nc = 2;
       g.ldw = 0;
-      if (nf == 1 && c.pkb == 24 && tiles * g.n_cb <= 256) {
+      if (nf == 1 && c.pkb == 24 && tiles * g.n_cb <= n_cu) {
         // a small tile that is alone on its CU because the grid has no second one to offer: four
         // more wavefronts take over the LDS-direct loads (measured 5-8 % faster on the 512-channel
         // 7x7 layer; slower where two workgroups share a CU)

@@ -47,7 +47,7 @@ def bf16_ulp(v):
 
 def run_float(inp: W.LayerInputs, gate: W.GateParams, *, in_dtype=B.CG_BF16, out_dtype=B.CG_F32,
               epilogue=B.CG_EPI_RELU, variant=B.CG_VARIANT_AUTO, affine=None, residual=None, delta_hi=None,
-              n_run=None, name="", check_counts=True, shuffle=False, tau_c=0.0):
+              n_run=None, name="", check_counts=True, shuffle=False, tau_c=0.0, tile_hint=0):
     """Runs the GPU library and the oracle; asserts parity; returns a Report.  A grouped input set
     (inp.grouped) runs the layer with channel grouping; shuffle stores y channel-shuffled."""
     s = inp.shape
@@ -64,7 +64,7 @@ def run_float(inp: W.LayerInputs, gate: W.GateParams, *, in_dtype=B.CG_BF16, out
                         stride=s.stride, pad=s.pad, epilogue=epilogue, variant=variant,
                         gate_mean=gate.mean if gate else None, gate_var=gate.var if gate else None,
                         delta=gate.delta if gate else None, delta_hi=delta_hi, gate_eps=gate.eps if gate else 0.0,
-                        groups=groups, shuffle=shuffle, tau_c=tau_c, **aff)
+                        groups=groups, shuffle=shuffle, tau_c=tau_c, tile_hint=tile_hint, **aff)
     n = s.n if n_run is None else n_run
     res_dev = None
     res_host = None
@@ -144,7 +144,7 @@ def compare_float(name, y, bitmap, counts, ref, c_out, out_dtype, variant_used, 
 
 
 def run_int8(q: W.Int8Inputs, thr, *, out_i8=False, epilogue=B.CG_EPI_RELU, variant=B.CG_VARIANT_AUTO,
-             rq=None, residual=None, rq_res_mult=0, n_run=None, name="", shuffle=False, tau_c=0.0):
+             rq=None, residual=None, rq_res_mult=0, n_run=None, name="", shuffle=False, tau_c=0.0, tile_hint=0):
     s = q.shape
     groups = s.groups if q.grouped else 1
     x = _dev(q.x, torch.int8)
@@ -155,7 +155,8 @@ def run_int8(q: W.Int8Inputs, thr, *, out_i8=False, epilogue=B.CG_EPI_RELU, vari
     layer = B.GatedConv(n_max=s.n, h=s.h, w=s.w, c_in=s.c_in, c_out=s.c_out, c_base=q.w_base.shape[-1],
                         w_base=wb, w_cond=wc, in_dtype=B.CG_I8, out_dtype=B.CG_I8 if out_i8 else B.CG_I32,
                         kh=k, kw=k, stride=s.stride, pad=s.pad, epilogue=epilogue, variant=variant,
-                        gate_thr_i32=thr, rq_res_mult=rq_res_mult, groups=groups, shuffle=shuffle, tau_c=tau_c, **rq)
+                        gate_thr_i32=thr, rq_res_mult=rq_res_mult, groups=groups, shuffle=shuffle, tau_c=tau_c,
+                        tile_hint=tile_hint, **rq)
     n = s.n if n_run is None else n_run
     res_dev = _dev(residual[:n], torch.int8) if residual is not None else None
     y, bitmap, counts = layer.forward(x[:n], residual=res_dev)

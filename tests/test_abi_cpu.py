@@ -73,18 +73,20 @@ def test_valid_descriptor_sizes_packed_buffer():
     (dict(w_base=None), B.CG_EINVAL),
     (dict(w_cond=None), B.CG_EINVAL),
     (dict(h=1, w=1, pad=0), B.CG_EINVAL),
-    (dict(in_dtype=B.CG_F32, variant=B.CG_VARIANT_MFMA), B.CG_EUNSUPPORTED),
+    (dict(in_dtype=B.CG_F32, variant=B.CG_VARIANT_TILE), B.CG_EUNSUPPORTED),
+    (dict(in_dtype=B.CG_F32, variant=B.CG_VARIANT_MFMA_ROWS), B.CG_EUNSUPPORTED),
+    (dict(variant=2), B.CG_EINVAL),                     # retired kernel families
+    (dict(variant=3), B.CG_EINVAL),
     (dict(groups=-1), B.CG_EINVAL),
     (dict(groups=2), B.CG_EINVAL),                      # c_base * groups != c_in
     (dict(groups=4, c_out=30), B.CG_EINVAL),            # groups does not divide c_out
     (dict(shuffle=1), B.CG_EINVAL),                     # shuffle without grouping
     (dict(groups=4, shuffle=2), B.CG_EINVAL),
-    (dict(groups=4, variant=B.CG_VARIANT_MFMA), B.CG_EUNSUPPORTED),
-    (dict(groups=4, variant=B.CG_VARIANT_MFMA_COMPACT), B.CG_EUNSUPPORTED),
     (dict(tau_c=-0.1), B.CG_EINVAL),
     (dict(tau_c=float("nan")), B.CG_EINVAL),
     (dict(tau_c=float("inf")), B.CG_EINVAL),
-    (dict(tau_c=0.5, variant=B.CG_VARIANT_MFMA), B.CG_EUNSUPPORTED),
+    (dict(tile_hint=1 << 12), B.CG_EINVAL),
+    (dict(tile_hint=-1), B.CG_EINVAL),
 ])
 def test_invalid_descriptors_are_rejected_without_a_gpu(over, code):
     d = make_desc(**over)

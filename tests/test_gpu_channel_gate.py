@@ -25,7 +25,8 @@ SHAPES = [
 ]
 
 
-@pytest.mark.parametrize("variant", [B.CG_VARIANT_NAIVE, B.CG_VARIANT_MFMA_ROWS], ids=["plain", "rows"])
+@pytest.mark.parametrize("variant", [B.CG_VARIANT_NAIVE, B.CG_VARIANT_MFMA_ROWS, B.CG_VARIANT_TILE],
+                         ids=["plain", "rows", "tile"])
 @pytest.mark.parametrize("shape", SHAPES, ids=[s.name for s in SHAPES])
 def test_channel_gate_int8_bit_exact(shape, variant):
     q = W.quantize_int8(W.make_inputs(shape, 7000 + shape.c_out, kind="coherent", rho=0.35))
@@ -39,7 +40,8 @@ def test_channel_gate_int8_bit_exact(shape, variant):
     assert fr[0] > 0.05
 
 
-@pytest.mark.parametrize("variant", [B.CG_VARIANT_NAIVE, B.CG_VARIANT_MFMA_ROWS], ids=["plain", "rows"])
+@pytest.mark.parametrize("variant", [B.CG_VARIANT_NAIVE, B.CG_VARIANT_MFMA_ROWS, B.CG_VARIANT_TILE],
+                         ids=["plain", "rows", "tile"])
 @pytest.mark.parametrize("shape", SHAPES[:3], ids=[s.name for s in SHAPES[:3]])
 def test_channel_gate_bf16(shape, variant):
     inp = W.make_inputs(shape, 7100 + shape.c_out, kind="coherent", rho=0.3, round_bf16=True)
@@ -59,7 +61,7 @@ def test_channel_gate_grouped_shuffled_with_epilogue():
     thr = W.calibrate_gate_int8(q, 0.35, sample_images=None)
     rq = W.requant_params(q, rng)
     res = rng.integers(-128, 128, (shape.n, shape.ho, shape.wo, shape.c_out)).astype(np.int8)
-    for variant in (B.CG_VARIANT_NAIVE, B.CG_VARIANT_MFMA_ROWS):
+    for variant in (B.CG_VARIANT_NAIVE, B.CG_VARIANT_MFMA_ROWS, B.CG_VARIANT_TILE):
         _say(P.run_int8(q, thr, variant=variant, tau_c=0.35, shuffle=True, out_i8=True, rq=rq, residual=res,
                         rq_res_mult=1 << 14, epilogue=B.CG_EPI_RESIDUAL | B.CG_EPI_RELU,
                         name="grouped shuffled requant tau_c=0.35 variant=%d" % variant))
@@ -95,16 +97,3 @@ def test_channel_gate_counts_without_bitmap_and_repeat():
         assert np.array_equal(cnt.cpu().numpy().view(np.uint32), ref["counts"])
         assert np.array_equal(y.cpu().numpy(), ref["y"])
     layer.close()
-
-
-def test_channel_gate_not_offered_by_older_kernels():
-    import torch
-    shape = SHAPES[0]
-    w = torch.zeros((shape.c_out, 3, 3, shape.c_base), dtype=torch.int8, device="cuda")
-    wc = torch.zeros((shape.c_out, 3, 3, shape.c_in - shape.c_base), dtype=torch.int8, device="cuda")
-    for variant in (B.CG_VARIANT_MFMA, B.CG_VARIANT_MFMA_COMPACT):
-        with pytest.raises(B.CGError) as e:
-            B.GatedConv(n_max=1, h=shape.h, w=shape.w, c_in=shape.c_in, c_out=shape.c_out, c_base=shape.c_base,
-                        w_base=w, w_cond=wc, in_dtype=B.CG_I8, out_dtype=B.CG_I32,
-                        gate_thr_i32=np.zeros(shape.c_out, np.int32), variant=variant, tau_c=0.5)
-        assert e.value.code == B.CG_EUNSUPPORTED

@@ -95,7 +95,8 @@ def test_maxpool_bit_exact(n, h, w, c):
     assert np.array_equal(y.float().cpu().numpy().astype(np.float64), O.maxpool3x3s2(x))     # a maximum of bf16 values is exact
 
 
-@pytest.mark.parametrize("n,hw,c,classes", [(4, 49, 512, 1000), (2, 16, 64, 10), (1, 1, 24, 7)])
+@pytest.mark.parametrize("n,hw,c,classes", [(4, 49, 512, 1000), (2, 16, 64, 10), (1, 1, 24, 7),
+                                              (2, 9, 640, 33), (2, 5, 768, 12), (1, 4, 1200, 9)])
 def test_avgpool_fc(n, hw, c, classes):
     rng = np.random.default_rng(hw + classes)
     x = _bf16(np.maximum(rng.standard_normal((n, hw, c)), 0))
@@ -119,7 +120,7 @@ def test_shortcut_conv_1x1_stride2_dense(c_in, c_out, hw):
     aff = dict(scale0=rng.uniform(0.5, 1.5, c_out), shift0=rng.normal(0, 0.1, c_out),
                scale1=rng.uniform(0.5, 1.5, c_out), shift1=rng.normal(0, 0.1, c_out))
     rep = P.run_float(inp, None, out_dtype=B.CG_BF16, epilogue=B.CG_EPI_AFFINE, affine=aff, name=shape.name)
-    assert rep.variant == B.CG_VARIANT_MFMA and rep.fired_frac == 0.0
+    assert rep.variant == B.CG_VARIANT_TILE and rep.fired_frac == 0.0
 
 
 @pytest.mark.parametrize("n,hw,c_in,c_out,stride", [(2, 56, 64, 128, 2), (3, 28, 128, 256, 2), (2, 14, 256, 512, 2),

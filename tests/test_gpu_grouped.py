@@ -53,7 +53,8 @@ def test_rows_grouped_int8_bit_exact(shape):
     assert 0.1 < rep.fired_frac < 0.6
 
 
-@pytest.mark.parametrize("variant", [B.CG_VARIANT_NAIVE, B.CG_VARIANT_MFMA_ROWS], ids=["plain", "rows"])
+@pytest.mark.parametrize("variant", [B.CG_VARIANT_NAIVE, B.CG_VARIANT_MFMA_ROWS, B.CG_VARIANT_TILE],
+                         ids=["plain", "rows", "tile"])
 @pytest.mark.parametrize("shape", [GROUPED[0], GROUPED[4]], ids=["one_group_per_block", "two_groups_per_block"])
 def test_grouped_shuffle_and_epilogues(shape, variant):
     rng = np.random.default_rng(91)
@@ -114,13 +115,13 @@ def test_grouped_delta_infinite(delta, frac):
 
 
 def test_grouped_kernels_agree_bit_for_bit_int8():
-    """Plain and row-tiled kernels on the same grouped int8 layer: identical outputs, decisions, counts."""
+    """Plain, row-tiled and large-tile kernels on the same grouped int8 layer: identical outputs, decisions, counts."""
     import torch
     for shape in (GROUPED[0], GROUPED[4]):
         q = W.quantize_int8(W.make_inputs(shape, 81, kind="coherent", rho=0.35, grouped=True))
         thr = W.calibrate_gate_int8(q, 0.35, sample_images=None)
         outs = []
-        for variant in (B.CG_VARIANT_NAIVE, B.CG_VARIANT_MFMA_ROWS):
+        for variant in (B.CG_VARIANT_NAIVE, B.CG_VARIANT_MFMA_ROWS, B.CG_VARIANT_TILE):
             layer = B.GatedConv(n_max=shape.n, h=shape.h, w=shape.w, c_in=shape.c_in, c_out=shape.c_out,
                                 c_base=shape.c_base, stride=shape.stride, pad=shape.pad,
                                 w_base=torch.from_numpy(q.w_base).cuda(), w_cond=torch.from_numpy(q.w_cond).cuda(),
@@ -130,19 +131,6 @@ def test_grouped_kernels_agree_bit_for_bit_int8():
             outs.append([t.cpu() for t in layer.forward(torch.from_numpy(q.x).cuda())])
             torch.cuda.synchronize()
             layer.close()
-        for u, v in zip(*outs):
-            assert torch.equal(u, v)
-
-
-def test_grouping_not_offered_by_older_kernels():
-    import torch
-    shape = GROUPED[0]
-    w = torch.zeros((shape.c_out, 3, 3, shape.c_base), dtype=torch.bfloat16, device="cuda")
-    wc = torch.zeros((shape.c_out, 3, 3, shape.c_in - shape.c_base), dtype=torch.bfloat16, device="cuda")
-    z = np.zeros(shape.c_out, np.float32)
-    for variant in (B.CG_VARIANT_MFMA, B.CG_VARIANT_MFMA_COMPACT):
-        with pytest.raises(B.CGError) as e:
-            B.GatedConv(n_max=1, h=shape.h, w=shape.w, c_in=shape.c_in, c_out=shape.c_out, c_base=shape.c_base,
-                        w_base=w, w_cond=wc, in_dtype=B.CG_BF16, out_dtype=B.CG_BF16, gate_mean=z, gate_var=z + 1,
-                        delta=z, variant=variant, groups=shape.groups)
-        assert e.value.code == B.CG_EUNSUPPORTED
+        for other in outs[1:]:
+            for u, v in zip(outs[0], other):
+                assert torch.equal(u, v)

@@ -15,13 +15,11 @@ def _say(rep):
     return rep
 
 
-VARIANTS = [B.CG_VARIANT_MFMA, B.CG_VARIANT_MFMA_COMPACT, B.CG_VARIANT_MFMA_ROWS]
-VNAMES = ["blockskip", "compact", "rows"]
+VARIANTS = [B.CG_VARIANT_MFMA_ROWS, B.CG_VARIANT_TILE]
+VNAMES = ["rows", "tile"]
 
 
 def _supported(shape, variant, int8=False):
-    if variant == B.CG_VARIANT_MFMA_COMPACT:
-        return shape.k == 3
     if variant == B.CG_VARIANT_MFMA_ROWS:      # 3x3, K stages of two 16-byte channel chunks (a one-chunk base group is padded)
         two_chunks = 32 if int8 else 16
         whole = shape.c_base % two_chunks == 0 and (shape.c_in - shape.c_base) % two_chunks == 0
@@ -55,7 +53,7 @@ SMALL = [
 @pytest.mark.parametrize("shape", SMALL, ids=[s.name for s in SMALL])
 def test_mfma_bf16_matches_oracle(shape, variant):
     if not _supported(shape, variant):
-        pytest.skip("shape outside this kernel family (1x1, or channel groups it cannot stage)")
+        pytest.skip("the row-tiled kernel takes 3x3 layers with 32-byte channel groups; the tile kernel covers the rest")
     inp = W.make_inputs(shape, 1000 + shape.c_out + shape.h, kind="coherent", rho=0.3, round_bf16=True)
     gate = W.calibrate_gate(inp, 0.30, sample_images=None)
     rep = _say(P.run_float(inp, gate, in_dtype=B.CG_BF16, out_dtype=B.CG_F32, variant=variant,
@@ -68,7 +66,7 @@ def test_mfma_bf16_matches_oracle(shape, variant):
 @pytest.mark.parametrize("shape", SMALL, ids=[s.name for s in SMALL])
 def test_mfma_int8_bit_exact(shape, variant):
     if not _supported(shape, variant, int8=True):
-        pytest.skip("shape outside this kernel family (1x1, or channel groups it cannot stage)")
+        pytest.skip("the row-tiled kernel takes 3x3 layers with 32-byte channel groups; the tile kernel covers the rest")
     if shape.c_base % 16:
         pytest.skip("int8 matrix-core path needs 16-channel groups")
     inp = W.make_inputs(shape, 2000 + shape.c_out + shape.h, kind="coherent", rho=0.35)
@@ -154,7 +152,7 @@ def test_mfma_matches_naive_kernel_decisions():
     q = W.quantize_int8(W.make_inputs(shape, 81, kind="coherent", rho=0.35))
     thr = W.calibrate_gate_int8(q, 0.35, sample_images=None)
     outs = []
-    for variant in (B.CG_VARIANT_NAIVE, B.CG_VARIANT_MFMA, B.CG_VARIANT_MFMA_COMPACT, B.CG_VARIANT_MFMA_ROWS):
+    for variant in (B.CG_VARIANT_NAIVE, B.CG_VARIANT_MFMA_ROWS, B.CG_VARIANT_TILE):
         x = torch.from_numpy(q.x).cuda()
         layer = B.GatedConv(n_max=2, h=28, w=28, c_in=128, c_out=128, c_base=32,
                             w_base=torch.from_numpy(q.w_base).cuda(), w_cond=torch.from_numpy(q.w_cond).cuda(),
