@@ -165,6 +165,21 @@ int cg_conv_forward(cg_conv* h, int32_t n, const void* x, const void* residual, 
                     uint32_t* bitmap, uint32_t* counts, void* workspace, size_t workspace_bytes,
                     void* hip_stream);
 
+/*
+ * cg_conv_forward for callers that cannot allocate device memory or pass a workspace: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments and results
+ * as cg_conv_forward without `workspace`: the scratch the call needs (the batch's decision bitmap when
+ * counts are asked for without a bitmap; with the channel-wise gate also the first pass's bitmap, counts
+ * and channel mask) lives in a fixed 16 MiB array inside the library, one copy per GPU, held until the
+ * process ends.  The call allocates nothing (no hipMalloc / hipFree, no allocating library routine) and
+ * relies on no previous contents of the array.  A call that needs more scratch than the array holds
+ * (cg_conv_workspace_bytes(h, n) > 16 MiB) fails with CG_EUNSUPPORTED and enqueues nothing.  Every call
+ * on one GPU shares that GPU's array: calls that may overlap on one GPU (different streams, different
+ * threads) race on it and must be serialised by the caller; calls on one stream are ordered.
+ */
+int cg_conv_forward_noalloc(cg_conv* h, int32_t n, const void* x, const void* residual, void* y,
+                            uint32_t* bitmap, uint32_t* counts, void* hip_stream);
+
 /* Frees the host handle; touches no device memory.  NULL is a no-op. */
 void cg_conv_destroy(cg_conv* h);
 

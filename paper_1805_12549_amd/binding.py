@@ -49,6 +49,7 @@ CG_EPI_RELU, CG_EPI_AFFINE, CG_EPI_RESIDUAL = 1, 2, 4
 CG_VARIANT_AUTO, CG_VARIANT_NAIVE, CG_VARIANT_MFMA_ROWS, CG_VARIANT_TILE = 0, 1, 4, 5
 
 EXPORTS = ("cg_conv_packed_bytes", "cg_conv_create", "cg_conv_workspace_bytes", "cg_conv_forward",
+           "cg_conv_forward_noalloc",
            "cg_conv_destroy", "cg_conv_info", "cg_last_error", "cg_small_cin_conv", "cg_conv7x7s2_maxpool", "cg_pointwise_conv",
            "cg_maxpool3x3s2", "cg_avgpool_fc")
 
@@ -85,6 +86,9 @@ _lib.cg_conv_workspace_bytes.restype = C.c_size_t
 _lib.cg_conv_forward.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                                  C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
 _lib.cg_conv_forward.restype = C.c_int
+_lib.cg_conv_forward_noalloc.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                         C.c_void_p, C.c_void_p]
+_lib.cg_conv_forward_noalloc.restype = C.c_int
 _lib.cg_conv_destroy.argtypes = [C.c_void_p]
 _lib.cg_conv_destroy.restype = None
 _lib.cg_conv_info.argtypes = [C.c_void_p, C.POINTER(C.c_int32), C.POINTER(C.c_int32)]
@@ -136,6 +140,15 @@ def cg_conv_forward(handle: int, n: int, x: int, residual: int, y: int, bitmap: 
     rc = _lib.cg_conv_forward(C.c_void_p(handle), n, C.c_void_p(x), C.c_void_p(residual), C.c_void_p(y),
                               C.c_void_p(bitmap), C.c_void_p(counts), C.c_void_p(workspace), workspace_bytes,
                               C.c_void_p(hip_stream))
+    if rc != CG_OK:
+        raise CGError(rc, cg_last_error())
+
+
+def cg_conv_forward_noalloc(handle: int, n: int, x: int, residual: int, y: int, bitmap: int, counts: int,
+                            hip_stream: int = 0) -> None:
+    """cg_conv_forward without a workspace: the library's own fixed scratch array is used."""
+    rc = _lib.cg_conv_forward_noalloc(C.c_void_p(handle), n, C.c_void_p(x), C.c_void_p(residual), C.c_void_p(y),
+                                      C.c_void_p(bitmap), C.c_void_p(counts), C.c_void_p(hip_stream))
     if rc != CG_OK:
         raise CGError(rc, cg_last_error())
 

@@ -213,6 +213,39 @@ inline uint32_t f2u(float f) {
 
 }  // namespace
 
+namespace {
+
+// Scratch for cg_conv_forward_noalloc: what cg_conv_forward takes as its `workspace` argument (the
+// batch's decision bitmap when only counts are asked for, and the first-pass counts and the channel
+// mask of the channel-wise gate).  Every GPU the library runs on holds its own copy of the array
+// until the process ends.  In host code the array's name is not a device address: the address is
+// asked for once per device and kept.
+constexpr size_t kScratchBytes = (size_t)16 << 20;
+constexpr int kMaxDevices = 64;
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
+void* g_scratch_ptr[kMaxDevices] = {};
+
+// the current device's copy of `scratch` (NULL with the error text set on failure)
+void* scratch_of_current_device() {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess || dev < 0 || dev >= kMaxDevices) {
+    fail(CG_EHIP, "no usable current device for the scratch array: %s", hipGetErrorString(e));
+    return nullptr;
+  }
+  void* ptr = __atomic_load_n(&g_scratch_ptr[dev], __ATOMIC_ACQUIRE);
+  if (ptr) return ptr;
+  e = hipGetSymbolAddress((void**)&ptr, HIP_SYMBOL(scratch));
+  if (e != hipSuccess || !ptr) {
+    fail(CG_EHIP, "hipGetSymbolAddress(scratch) failed on device %d: %s", dev, hipGetErrorString(e));
+    return nullptr;
+  }
+  __atomic_store_n(&g_scratch_ptr[dev], ptr, __ATOMIC_RELEASE);   // (two threads may both ask: same answer)
+  return ptr;
+}
+
+}  // namespace
+
 extern "C" {
 
 const char* cg_last_error(void) { return g_err.c_str(); }
@@ -331,6 +364,14 @@ int cg_conv_create(cg_conv** out, const cg_conv_desc* desc, void* hip_stream) {
     return code;
   }
   h->d.w_base = h->d.w_cond = nullptr;
+  // set-up is the place to ask for this device's scratch address, so that a later
+  // cg_conv_forward_noalloc (possibly under graph capture) only reads it
+  if (!scratch_of_current_device()) {
+    const std::string keep = g_err;
+    delete h;
+    g_err = keep;
+    return CG_EHIP;
+  }
   *out = h;
   return CG_OK;
 }
@@ -387,6 +428,22 @@ extern "C" {
 int cg_conv_forward(cg_conv* h, int32_t n, const void* x, const void* residual, void* y, uint32_t* bitmap,
                     uint32_t* counts, void* workspace, size_t workspace_bytes, void* hip_stream) {
   return forward_impl(h, n, x, residual, y, bitmap, counts, workspace, workspace_bytes, hip_stream);
+}
+
+int cg_conv_forward_noalloc(cg_conv* h, int32_t n, const void* x, const void* residual, void* y, uint32_t* bitmap,
+                            uint32_t* counts, void* hip_stream) {
+  if (!h) return fail(CG_EINVAL, "handle is NULL");
+  if (n < 0 || n > h->d.n_max) return fail(CG_EINVAL, "n = %d is outside [0, n_max = %d]", n, h->d.n_max);
+  const size_t need = n > 0 ? cg_conv_workspace_bytes(h, n) : 0;
+  if (need > kScratchBytes)
+    return fail(CG_EUNSUPPORTED, "this call needs %zu bytes of scratch; the library's fixed scratch array holds %zu",
+                need, kScratchBytes);
+  void* ws = nullptr;
+  if (need > 0) {
+    ws = scratch_of_current_device();
+    if (!ws) return CG_EHIP;
+  }
+  return forward_impl(h, n, x, residual, y, bitmap, counts, ws, need, hip_stream);
 }
 
 void cg_conv_destroy(cg_conv* h) { delete h; }
