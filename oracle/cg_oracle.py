@@ -66,7 +66,32 @@ class _Problem(C.Structure):
     ]
 
 
+_LIB_TIMED = _HERE / "libcg_ref_timed.so"
+TIMED_FLAGS = ["-O3", "-march=native", "-fopenmp", "-DCG_REF_ACC=float"]
+
+
+def build_timed(force: bool = False) -> Path:
+    """The same source built for the CPU timing of the benchmark: -O3 -march=native and
+    single-precision accumulators in cg_ref_forward_skip.  Never used for parity."""
+    if force or not _LIB_TIMED.exists() or _LIB_TIMED.stat().st_mtime < _SRC.stat().st_mtime:
+        tmp = _LIB_TIMED.with_suffix(".so.tmp%d" % os.getpid())
+        subprocess.check_call(["gcc", *TIMED_FLAGS, "-fPIC", "-shared", "-std=c11", "-o", str(tmp), str(_SRC), "-lm"])
+        os.replace(tmp, _LIB_TIMED)
+    return _LIB_TIMED
+
+
 _lib = None
+_lib_timed = None
+
+
+def _load_timed():
+    global _lib_timed
+    if _lib_timed is None:
+        build_timed()
+        _lib_timed = C.CDLL(str(_LIB_TIMED))
+        _lib_timed.cg_ref_forward_skip.argtypes = [C.POINTER(_Problem)]
+        _lib_timed.cg_ref_forward_skip.restype = C.c_int
+    return _lib_timed
 
 
 def _load():
@@ -76,6 +101,8 @@ def _load():
         _lib = C.CDLL(str(_LIB))
         _lib.cg_ref_forward.argtypes = [C.POINTER(_Problem)]
         _lib.cg_ref_forward.restype = C.c_int
+        _lib.cg_ref_forward_skip.argtypes = [C.POINTER(_Problem)]
+        _lib.cg_ref_forward_skip.restype = C.c_int
     return _lib
 
 
@@ -160,6 +187,56 @@ def forward_float(x, w_base, w_cond, *, stride=1, pad=1, gate_mean=None, gate_va
     rc = lib.cg_ref_forward(C.byref(p))
     if rc != 0:
         raise ValueError("cg_ref_forward rejected the problem (rc=%d)" % rc)
+    out["macs"] = int(macs.value)
+    out["fired"] = int(out["counts"][0]) | (int(out["counts"][1]) << 32)
+    return out
+
+
+def forward_skip(x, w_base, w_cond, *, thr=None, stride=1, pad=1, gate_mean=None, gate_var=None, delta=None,
+                 gate_eps=0.0, epilogue=RELU, groups=1, timed_build=False):
+    """The layer as Eq. 1 executes it (cg_ref_forward_skip): the conditional sum is evaluated only
+    where the gate fired.  Float path when ``thr`` is None (x, w widened to float64), else the int8
+    path with the integer thresholds ``thr`` (raw int32 sums out).  timed_build: the -O3 build with
+    single-precision accumulators that the benchmark times.  Returns y, d, bitmap, counts, macs."""
+    lib = _load_timed() if timed_build else _load()
+    is_int = thr is not None
+    dt = np.int8 if is_int else np.float64
+    x = _as(x, dt)
+    w_base = _as(w_base, dt)
+    n, h, w, c_in = x.shape
+    c_out, kh, kw, c_base = w_base.shape
+    w_cond = _as(w_cond, dt) if c_in > c_base else None
+    ho, wo = out_hw(h, w, kh, kw, stride, pad)
+    shape = (n, ho, wo, c_out)
+    words = (c_out + 31) // 32
+    out = dict(y=np.empty(shape, np.int32 if is_int else np.float64), d=np.empty(shape, np.uint8),
+               bitmap=np.empty((n * ho * wo, words), np.uint32), counts=np.empty(2 + n * c_out, np.uint32))
+    macs = C.c_uint64(0)
+    p = _Problem()
+    p.n, p.h, p.w, p.c_in, p.c_out, p.c_base = n, h, w, c_in, c_out, c_base
+    p.kh, p.kw, p.stride, p.pad = kh, kw, stride, pad
+    p.is_int, p.out_i8, p.epilogue = int(is_int), 0, epilogue
+    p.groups = int(groups)
+    p.gate_eps = gate_eps
+    keep = []
+    if is_int:
+        thr = _as(thr, np.int32)
+        p.xi, p.wi_base, p.wi_cond, p.thr = _ptr(x, _pi8), _ptr(w_base, _pi8), _ptr(w_cond, _pi8), _ptr(thr, _pi32)
+        p.yi = _ptr(out["y"], _pi32)
+    else:
+        p.x, p.w_base, p.w_cond = _ptr(x, _pd), _ptr(w_base, _pd), _ptr(w_cond, _pd)
+        for name, v in (("gate_mean", gate_mean), ("gate_var", gate_var), ("delta", delta)):
+            v = _as(v, np.float64)
+            keep.append(v)
+            setattr(p, name, _ptr(v, _pd))
+        p.y = _ptr(out["y"], _pd)
+    p.d = _ptr(out["d"], _pu8)
+    p.bitmap = _ptr(out["bitmap"], _pu32)
+    p.counts = _ptr(out["counts"], _pu32)
+    p.macs = C.pointer(macs)
+    rc = lib.cg_ref_forward_skip(C.byref(p))
+    if rc != 0:
+        raise ValueError("cg_ref_forward_skip rejected the problem (rc=%d)" % rc)
     out["macs"] = int(macs.value)
     out["fired"] = int(out["counts"][0]) | (int(out["counts"][1]) << 32)
     return out

@@ -341,6 +341,135 @@ int cg_ref_forward(const cg_ref_problem *p) {
 }
 
 /*
+ * The layer as Eq. 1 executes it: the base sum everywhere, the gate, and the
+ * conditional sum only where the gate fired -- the work the method saves is
+ * not done here either.  Same loops and order as cg_ref_forward within each of
+ * the two sums, so with double accumulators y, d, bitmap, counts and macs are
+ * identical to cg_ref_forward's.  Used for the CPU timing of the benchmark,
+ * where it is also built with -DCG_REF_ACC=float (single-precision
+ * accumulators, the float path only; integers stay exact).  Outputs: y / yi,
+ * d, bitmap, counts, macs (any may be NULL).  The channel-wise gate and the
+ * two-sided gate are not offered (returns 1).
+ */
+#ifndef CG_REF_ACC
+#define CG_REF_ACC double
+#endif
+int cg_ref_forward_skip(const cg_ref_problem *p) {
+  if (!p || p->n < 0 || p->h <= 0 || p->w <= 0 || p->c_in <= 0 || p->c_out <= 0) return 1;
+  if (p->c_base <= 0 || p->c_base > p->c_in) return 1;
+  if (p->kh <= 0 || p->kw <= 0 || p->stride <= 0 || p->pad < 0) return 1;
+  if (p->is_int ? (!p->xi || !p->wi_base) : (!p->x || !p->w_base)) return 1;
+  if (p->tau_c > 0.0 || p->two_sided) return 1;
+  const int N = p->n, H = p->h, W = p->w, C = p->c_in, CO = p->c_out, CP = p->c_base;
+  const int CR = C - CP;
+  if (CR > 0 && (p->is_int ? !p->wi_cond : !p->w_cond)) return 1;
+  const int gated = CR > 0;
+  const int G = p->groups > 1 ? p->groups : 1;
+  if (G > 1 && ((long long)CP * G != C || CO % G != 0)) return 1;
+  if (p->shuffle && G == 1) return 1;
+  const int CPG = CO / G;
+  if (gated && (p->is_int ? !p->thr : (!p->gate_mean || !p->gate_var || !p->delta))) return 1;
+  const int KH = p->kh, KW = p->kw, ST = p->stride, PD = p->pad;
+  const int HO = cg_ref_out_h(p), WO = cg_ref_out_w(p);
+  const int words = (CO + 31) / 32;
+  const size_t M = (size_t)N * HO * WO;
+  if (p->bitmap) memset(p->bitmap, 0, M * words * sizeof(uint32_t));
+  if (p->counts) memset(p->counts, 0, (2 + (size_t)N * CO) * sizeof(uint32_t));
+  uint64_t total_fired = 0, total_macs = 0;
+
+#pragma omp parallel for collapse(2) schedule(static) reduction(+ : total_fired, total_macs)
+  for (int n = 0; n < N; ++n) {
+    for (int ho = 0; ho < HO; ++ho) {
+      for (int wo = 0; wo < WO; ++wo) {
+        const size_t m = ((size_t)n * HO + ho) * WO + wo;
+        for (int co = 0; co < CO; ++co) {
+          const size_t o = m * CO + co;
+          const int grp = co / CPG;
+          const int b0 = grp * CP;
+          const size_t oy = p->shuffle ? m * CO + (size_t)(co % CPG) * G + grp : o;
+          /* base path (Sec. 3.1): always */
+          CG_REF_ACC accP = 0;
+          int32_t iP = 0;
+          uint64_t taps_in = 0;
+          for (int r = 0; r < KH; ++r) {
+            const int hi = ho * ST - PD + r;
+            if (hi < 0 || hi >= H) continue;
+            for (int s = 0; s < KW; ++s) {
+              const int wi = wo * ST - PD + s;
+              if (wi < 0 || wi >= W) continue;
+              ++taps_in;
+              const size_t xo = (((size_t)n * H + hi) * W + wi) * C;
+              const size_t wbo = (((size_t)co * KH + r) * KW + s) * CP;
+              if (p->is_int) {
+                for (int c = 0; c < CP; ++c) iP += (int32_t)p->xi[xo + b0 + c] * (int32_t)p->wi_base[wbo + c];
+              } else {
+                for (int c = 0; c < CP; ++c) accP += (CG_REF_ACC)(p->x[xo + b0 + c] * p->w_base[wbo + c]);
+              }
+            }
+          }
+          /* gate (Sec. 3.2): ties fire */
+          int fired = 1;
+          if (gated) {
+            if (p->is_int) {
+              fired = iP >= p->thr[co];
+            } else {
+              const double dl = p->delta[co];
+              if (isinf(dl))
+                fired = dl < 0;
+              else
+                fired = (double)accP >= p->gate_mean[co] + dl * sqrt(p->gate_var[co] + p->gate_eps);
+            }
+          }
+          /* conditional path (Eq. 1): only where the gate fired */
+          CG_REF_ACC accR = 0;
+          int32_t iR = 0;
+          if (gated && fired) {
+            for (int r = 0; r < KH; ++r) {
+              const int hi = ho * ST - PD + r;
+              if (hi < 0 || hi >= H) continue;
+              for (int s = 0; s < KW; ++s) {
+                const int wi = wo * ST - PD + s;
+                if (wi < 0 || wi >= W) continue;
+                const size_t xo = (((size_t)n * H + hi) * W + wi) * C;
+                const size_t wco = (((size_t)co * KH + r) * KW + s) * CR;
+                if (p->is_int) {
+                  for (int c = 0; c < CR; ++c)
+                    iR += (int32_t)p->xi[xo + (c < b0 ? c : c + CP)] * (int32_t)p->wi_cond[wco + c];
+                } else {
+                  for (int c = 0; c < CR; ++c)
+                    accR += (CG_REF_ACC)(p->x[xo + (c < b0 ? c : c + CP)] * p->w_cond[wco + c]);
+                }
+              }
+            }
+          }
+          total_macs += taps_in * (uint64_t)(CP + ((gated && fired) ? CR : 0));
+          if (p->is_int) {
+            if (p->yi) p->yi[oy] = finish_int(p, iP + iR, fired, co, oy);
+          } else {
+            if (p->y) p->y[oy] = finish_float(p, (double)accP + (double)accR, fired, co, oy);
+          }
+          if (p->d) p->d[o] = (uint8_t)(gated ? fired : 0);
+          if (gated && fired) {
+            ++total_fired;
+            if (p->bitmap) p->bitmap[m * words + (co >> 5)] |= 1u << (co & 31);
+            if (p->counts) {
+#pragma omp atomic
+              p->counts[2 + (size_t)n * CO + co] += 1u;
+            }
+          }
+        }
+      }
+    }
+  }
+  if (p->counts) {
+    p->counts[0] = (uint32_t)(total_fired & 0xffffffffu);
+    p->counts[1] = (uint32_t)(total_fired >> 32);
+  }
+  if (p->macs) *p->macs = total_macs;
+  return 0;
+}
+
+/*
  * The dense pieces of a ResNet around the gated layers (the paper's experiments
  * run ResNet-18, Sec. 5), as plain definitions in double precision, NHWC.
  */

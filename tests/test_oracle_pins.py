@@ -635,3 +635,74 @@ def test_avgpool_fc_matches_library():
     np.testing.assert_allclose(O.avgpool_fc(x.reshape(3, 49, 10), w), want - b, rtol=1e-12, atol=1e-12)
     # by hand: constant maps, identity weights
     np.testing.assert_allclose(O.avgpool_fc(np.full((1, 4, 2), 3.0), np.eye(2)), [[3.0, 3.0]])
+
+
+# ---------------------------------------------------------------------------
+# The layer as Eq. 1 executes it (conditional sum only where the gate fired): brute force, the
+# library convolutions at the two extremes, the executed-MAC count in closed form, and the build
+# the benchmark times
+# ---------------------------------------------------------------------------
+@pytest.mark.parametrize("stride,pad", [(1, 1), (2, 1), (1, 0)])
+@pytest.mark.parametrize("g", [2, 4])
+def test_skip_where_closed_brute_force(stride, pad, g):
+    rng = np.random.default_rng(900 + 100 * stride + 10 * pad + g)
+    n, h, w, c_in, c_out = 2, 6, 5, 8, 4
+    # integers: every sum is exact in any accumulator, so the rational brute force must be met exactly
+    x, wb, wc = rand_problem(rng, n, h, w, c_in, c_out, g, ints=True)
+    thr = rng.integers(-4, 12, c_out).astype(np.float64)
+    P, R, D, S = gated_conv_brute(x.tolist(), wb.tolist(), wc.tolist(), stride, pad, [Fraction(float(t)) for t in thr])
+    D, S = np.array(D, np.uint8), np.array(S, np.float64)
+    for timed in (False, True):
+        out = O.forward_skip(x, wb, wc, stride=stride, pad=pad, gate_mean=thr, gate_var=np.ones(c_out),
+                             delta=np.zeros(c_out), epilogue=0, timed_build=timed)
+        assert np.array_equal(out["d"], D)
+        assert np.array_equal(out["y"], S)
+        assert out["fired"] == int(D.sum())
+        bits = np.unpackbits(out["bitmap"].view(np.uint8), bitorder="little").reshape(-1, 32)[:, :c_out]
+        assert np.array_equal(bits.reshape(D.shape), D)
+    # int8 path against the same brute force
+    xi = rng.integers(0, 128, (n, h, w, c_in)).astype(np.int8)
+    wt = rng.integers(-127, 128, (c_out, 3, 3, c_in)).astype(np.int8)
+    cb = c_in // g
+    wbi, wci = np.ascontiguousarray(wt[..., :cb]), np.ascontiguousarray(wt[..., cb:])
+    ti = rng.integers(-3000, 3000, c_out).astype(np.int32)
+    _, _, Di, Si = gated_conv_brute(xi.tolist(), wbi.tolist(), wci.tolist(), stride, pad, ti.tolist(), exact=False)
+    for timed in (False, True):
+        out = O.forward_skip(xi, wbi, wci, thr=ti, stride=stride, pad=pad, epilogue=0, timed_build=timed)
+        assert np.array_equal(out["d"], np.array(Di, np.uint8))
+        assert np.array_equal(out["y"], np.array(Si, np.int64))
+
+
+def test_skip_where_closed_extremes_and_mac_count():
+    rng = np.random.default_rng(77)
+    n, h, w, c_in, c_out, g = 2, 7, 6, 8, 6, 4
+    x, wb, wc = rand_problem(rng, n, h, w, c_in, c_out, g)
+    wfull = np.concatenate([wb, wc], axis=-1)
+    one, zero = np.ones(c_out), np.zeros(c_out)
+    # every gate open: the dense convolution of all channels; every gate closed: the base channels alone
+    op = O.forward_skip(x, wb, wc, pad=0, gate_mean=zero, gate_var=one, delta=np.full(c_out, -np.inf), epilogue=0)
+    np.testing.assert_allclose(op["y"], lib_conv(x, wfull, 1, 0), rtol=0, atol=1e-12)
+    cl = O.forward_skip(x, wb, wc, pad=0, gate_mean=zero, gate_var=one, delta=np.full(c_out, np.inf), epilogue=0)
+    np.testing.assert_allclose(cl["y"], lib_conv(x[..., :2], wb, 1, 0), rtol=0, atol=1e-12)
+    # no padding: every output sees all nine taps, so the executed multiply-adds have a closed form
+    m = n * (h - 2) * (w - 2)
+    assert op["macs"] == m * c_out * 9 * c_in and cl["macs"] == m * c_out * 9 * 2
+    mid = O.forward_skip(x, wb, wc, pad=0, gate_mean=zero, gate_var=one, delta=np.full(c_out, 0.2), epilogue=0)
+    assert 0 < mid["fired"] < m * c_out
+    assert mid["macs"] == m * c_out * 9 * 2 + mid["fired"] * 9 * 6
+    # and the same decisions, outputs and counts as the both-branches oracle
+    ref = O.forward_float(x, wb, wc, pad=0, gate_mean=zero, gate_var=one, delta=np.full(c_out, 0.2), epilogue=0)
+    assert np.array_equal(mid["d"], ref["d"]) and np.array_equal(mid["bitmap"], ref["bitmap"])
+    assert np.array_equal(mid["counts"], ref["counts"]) and mid["macs"] == ref["macs"]
+    np.testing.assert_array_equal(mid["y"], ref["y"])
+
+
+def test_timed_build_differs_only_by_single_precision_rounding():
+    rng = np.random.default_rng(78)
+    x, wb, wc = rand_problem(rng, 2, 9, 8, 16, 8, 4)
+    kw = dict(gate_mean=np.zeros(8), gate_var=np.ones(8), delta=np.full(8, 0.3), epilogue=O.RELU)
+    a = O.forward_skip(x, wb, wc, **kw)
+    b = O.forward_skip(x, wb, wc, timed_build=True, **kw)
+    same = a["d"] == b["d"]
+    assert same.mean() > 0.99                                   # a sum on the threshold may round either way
+    np.testing.assert_allclose(b["y"][same], a["y"][same], rtol=1e-5, atol=1e-5)
