@@ -508,60 +508,56 @@ __global__ __launch_bounds__(kNT) void gated_conv_tile_kernel(Params p, TilePlan
     lds_barrier();
   };
 
-  // ---- combine: R (compacted rows) goes through LDS, 32 rows at a time, to the lanes that hold P;
-  // the conditional sum is dropped where that channel did not fire (Eq. 1).  No load is in flight.
+  // ---- combine: R (the pass's compacted rows) goes through LDS to the lanes that hold P; the
+  // conditional sum is dropped where that channel did not fire (Eq. 1).  No load is in flight and
+  // the stage buffers are free: the whole R tile of the pass lies in them at once.
   auto combine = [&](int pass0) __attribute__((always_inline)) {
     asm volatile("s_nop 7\n\ts_nop 7\n\ts_nop 7" ::: "memory");
     constexpr int RS = C::RS;
-    const int left = n_act - pass0;
+    static_assert(C::CAP * RS <= NB * C::SZ, "the R tile of a pass must fit the stage buffers");
 #pragma unroll
     for (int k = 0; k < FPR; ++k) {
-#pragma nounroll
-      for (int w = 0; w < WM; ++w) {
-        const int first = (k * WM + w) * 32;          // first listed pixel of this slice, within the pass
-        if (first >= left) break;
-        if (w == wm) {
-          char* row = buf0 + lj * RS + (wn * 64 + lh * 16) * 4;
+      if (k < nl) {
+        char* row = ring + ((k * WM + wm) * 32 + lj) * RS + (wn * 64 + lh * 16) * 4;
 #pragma unroll
-          for (int fl = 0; fl < 2; ++fl)
+        for (int fl = 0; fl < 2; ++fl)
 #pragma unroll
-            for (int q4 = 0; q4 < 4; ++q4) {
-              i32x4 v;
+          for (int q4 = 0; q4 < 4; ++q4) {
+            i32x4 v;
 #pragma unroll
-              for (int e = 0; e < 4; ++e) {
-                const acc_t rv = accR[k][fl][4 * q4 + e];
-                v[e] = bits_of(rv);
-              }
-              *(i32x4*)(row + fl * 128 + q4 * 16) = v;
+            for (int e = 0; e < 4; ++e) {
+              const acc_t rv = accR[k][fl][4 * q4 + e];
+              v[e] = bits_of(rv);
             }
-        }
-        __syncthreads();
-#pragma unroll
-        for (int fp = 0; fp < FP; ++fp) {
-          // a pixel without a row in this slice adds nothing; a fragment with no such pixel is skipped
-          const int r = (int)rank[pix[fp]] - pass0 - first;
-          const bool ok = dlane[fp] != 0u && r >= 0 && r < 32;
-          if (__ballot(ok) != 0ull) {
-            const unsigned dm = ok ? dlane[fp] : 0u;
-            const char* row = buf0 + (ok ? r : 0) * RS + (wn * 64 + lh * 16) * 4;
-#pragma unroll
-            for (int fl = 0; fl < 2; ++fl)
-#pragma unroll
-              for (int q4 = 0; q4 < 4; ++q4) {
-                const i32x4 v = *(const i32x4*)(row + fl * 128 + q4 * 16);
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                  const bool on = (dm >> (16 * fl + 4 * q4 + e)) & 1u;
-                  acc_t rv;
-                  set_bits(v[e], rv);
-                  accP[fp][fl][4 * q4 + e] += on ? rv : (acc_t)0;
-                }
-              }
+            *(i32x4*)(row + fl * 128 + q4 * 16) = v;
           }
-        }
-        __syncthreads();
       }
     }
+    __syncthreads();
+#pragma unroll
+    for (int fp = 0; fp < FP; ++fp) {
+      // a pixel without a row in this pass adds nothing; a fragment with no such pixel is skipped
+      const int r = (int)rank[pix[fp]] - pass0;
+      const bool ok = dlane[fp] != 0u && r >= 0 && r < C::CAP;
+      if (__ballot(ok) != 0ull) {
+        const unsigned dm = ok ? dlane[fp] : 0u;
+        const char* row = ring + (ok ? r : 0) * RS + (wn * 64 + lh * 16) * 4;
+#pragma unroll
+        for (int fl = 0; fl < 2; ++fl)
+#pragma unroll
+          for (int q4 = 0; q4 < 4; ++q4) {
+            const i32x4 v = *(const i32x4*)(row + fl * 128 + q4 * 16);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+              const bool on = (dm >> (16 * fl + 4 * q4 + e)) & 1u;
+              acc_t rv;
+              set_bits(v[e], rv);
+              accP[fp][fl][4 * q4 + e] += on ? rv : (acc_t)0;
+            }
+          }
+      }
+    }
+    __syncthreads();
   };
 
   // ---- the stage pipeline ---------------------------------------------------------------------------
