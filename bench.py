@@ -43,7 +43,10 @@ def parse():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--batch", type=int, default=64)
     ap.add_argument("--rho", type=float, default=0.30)
-    ap.add_argument("--kind", default="coherent", choices=["coherent", "literal", "iid"])
+    ap.add_argument("--kind", default=None, choices=["coherent", "literal", "iid"],
+                    help="gate maps: spatially clustered across channels (coherent, the default), the literal recipe "
+                         "(zero-mean weights: unclustered across channels) or i.i.d. inputs; --sweep walks coherent and "
+                         "literal unless one is named")
     ap.add_argument("--no-dense", action="store_true", help="skip the dense comparator (for kernel profiles)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline")
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying a HIP graph")
@@ -199,7 +202,7 @@ def run_sweep(args, shapes, variant):
     import torch
     rhos = [0.1, 0.3, 0.5, 0.7, 0.9]
     rows = []
-    for kind in ("coherent", "literal"):
+    for kind in (("coherent", "literal") if args.kind is None else (args.kind,)):
         for li, s0 in enumerate(shapes):
             for G in (2, 4, 8):
                 s = replace(s0, groups=G)
@@ -248,6 +251,7 @@ def main():
 
     if args.sweep:
         rows = run_sweep(args, shapes, variant)
+        args.kind = args.kind or "coherent + literal"
         print(json.dumps({"metric": "crossover firing rate of the gated layer against the dense convolution",
                           "n_gpus": 1, "dtype": args.dtype, "data": "synthetic",
                           "config": {"workload": "ImageNet-shaped ResNet-18 3x3 layers, batch %d, %s; firing rate x base "
@@ -255,6 +259,7 @@ def main():
                                                  % (args.batch, args.dtype), "sweep": rows}}), flush=True)
         return
 
+    args.kind = args.kind or "coherent"
     layers = [Layer(args, s, li, args.rho, args.kind, variant, want_dense=not args.no_dense)
               for li, s in enumerate(shapes)]
     torch.cuda.synchronize()
