@@ -50,6 +50,8 @@ def parse():
     ap.add_argument("--no-dense", action="store_true", help="skip the dense comparator (for kernel profiles)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline")
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying a HIP graph")
+    ap.add_argument("--warm", action="store_true",
+                    help="two buffer sets per layer instead of a rotation past the 256 MB Infinity Cache (warm-cache regime)")
     ap.add_argument("--variant", default="auto", choices=["auto", "rows", "tile"],
                     help="kernel family (auto = what the library picks)")
     ap.add_argument("--dtype", default="bf16", choices=["bf16", "int8"],
@@ -127,6 +129,8 @@ class Layer:
         x_bytes = s.n * s.h * s.w * s.c_in * eb
         y_bytes = s.m * s.c_out * eb
         self.nset = min(24, max(2, int(np.ceil(600e6 / (x_bytes + y_bytes)))))    # rotate past the 256 MB infinity cache
+        if args.warm:
+            self.nset = 2
         x0 = torch.from_numpy(inp.x).to(dev).to(tdt)
         self.xs = [x0] + [x0.clone() for _ in range(self.nset - 1)]
         self.ys = [torch.empty((s.n, s.ho, s.wo, s.c_out), dtype=tdt, device=dev) for _ in range(self.nset)]
@@ -198,11 +202,16 @@ def crossover(rhos, us_gated, us_dense):
     return "> %.2f (always faster)" % rhos[-1]
 
 
+# how often each 3x3 shape occurs among the sixteen residual-block convolutions of ResNet-18
+CONVS_OF_SHAPE = {"64@56": 4, "128@28": 3, "256@14": 3, "512@7": 3}
+
+
 def run_sweep(args, shapes, variant):
     import torch
     rhos = [0.1, 0.3, 0.5, 0.7, 0.9]
     rows = []
     for kind in (("coherent", "literal") if args.kind is None else (args.kind,)):
+        first_row = len(rows)
         for li, s0 in enumerate(shapes):
             for G in (2, 4, 8):
                 s = replace(s0, groups=G)
@@ -225,6 +234,25 @@ def run_sweep(args, shapes, variant):
                 print("sweep %-9s %-13s 1/G=1/%d dense %6.2f us  gated %s  crossover %s" %
                       (kind, s.name, G, us_dense, " ".join("%6.2f" % v for v in us_g), rows[-1]["crossover_rho"]),
                       file=sys.stderr, flush=True)
+        # the sixteen gated convolutions of the network together, per base fraction
+        for G in (2, 4, 8):
+            mine = [r for r in rows[first_row:] if r["base_fraction"] == "1/%d" % G and r["layer"] != "network"]
+            if len(mine) != len(shapes) or len(shapes) != 7:
+                continue
+            mult = [CONVS_OF_SHAPE.get(r["layer"], 1) for r in mine]
+            sum_g = [sum(m * r["us_gated"][i] for m, r in zip(mult, mine)) for i in range(len(rhos))]
+            sum_d = sum(m * r["us_dense"] for m, r in zip(mult, mine))
+            wsum = float(sum(m * s.m * s.c_out for m, s in zip(mult, shapes)))
+            rho_net = [round(sum(m * r["rho"][i] * s.m * s.c_out for m, r, s in zip(mult, mine, shapes)) / wsum, 3)
+                       for i in range(len(rhos))]
+            rows.append(dict(layer="network", maps=kind, base_fraction="1/%d" % G,
+                             what="sum over the 16 residual-block 3x3 convolutions of ResNet-18 (shape multiplicities "
+                                  "4/3/3/3/1/1/1), each on its own input", rho_target=rhos, rho=rho_net,
+                             us_gated=[round(v, 1) for v in sum_g], us_dense=round(sum_d, 1),
+                             crossover_rho=crossover(rho_net, sum_g, sum_d)))
+            print("sweep %-9s %-13s 1/G=1/%d dense %6.1f us  gated %s  crossover %s" %
+                  (kind, "16 convs", G, sum_d, " ".join("%6.1f" % v for v in sum_g), rows[-1]["crossover_rho"]),
+                  file=sys.stderr, flush=True)
     return rows
 
 
@@ -254,9 +282,12 @@ def main():
         args.kind = args.kind or "coherent + literal"
         print(json.dumps({"metric": "crossover firing rate of the gated layer against the dense convolution",
                           "n_gpus": 1, "dtype": args.dtype, "data": "synthetic",
-                          "config": {"workload": "ImageNet-shaped ResNet-18 3x3 layers, batch %d, %s; firing rate x base "
-                                                 "fraction sweep, clustered (coherent) and unclustered (literal) maps"
-                                                 % (args.batch, args.dtype), "sweep": rows}}), flush=True)
+                          "config": {"workload": "ImageNet-shaped ResNet-18 3x3 layers, batch %d, %s, %s; firing rate x "
+                                                 "base fraction sweep, clustered (coherent) and unclustered (literal) maps"
+                                                 % (args.batch, args.dtype, "scale/shift by decision + residual + ReLU"
+                                                    if args.fused_epilogue else "ReLU epilogue"),
+                                     "cache": "warm" if args.warm else "cold (buffers rotated past the Infinity Cache)",
+                                     "sweep": rows}}), flush=True)
         return
 
     args.kind = args.kind or "coherent"
@@ -380,6 +411,7 @@ def main():
                                 (", fused scale/shift + residual + ReLU epilogue" if args.fused_epilogue else "") +
                                 (", channel-wise gate tau_c=%.2f" % args.tau_c if args.tau_c > 0 else ""), len(layers)),
                    "launch": "eager" if args.no_graph else "hip graph replay",
+                   "cache": "warm (two buffer sets per layer)" if args.warm else "cold (buffers rotated past the 256 MB Infinity Cache)",
                    "timed_region": "exactly %d steps, timed %d times, median" % (steps, repeats),
                    "sum_us_gated": round(t_kernel_us, 2),
                    "sum_us_dense": None if args.no_dense else round(sum(L.us_dense for L in layers), 2),
