@@ -917,6 +917,44 @@ __global__ void bitmap_counts_kernel(const uint32_t* __restrict__ bitmap, int wo
   }
 }
 
+// The same for feature maps of a few pixels (fully connected layers are 1x1 maps): one thread per
+// (image, bitmap word) walks the map's pixels, so a batch of thousands of tiny maps is a few hundred
+// blocks and one atomic per block instead of one block and one atomic per word.
+__global__ void bitmap_counts_small_kernel(const uint32_t* __restrict__ bitmap, int words, int hw, int c_out,
+                                           long long items, uint32_t* __restrict__ counts,
+                                           uint32_t* __restrict__ mask, uint32_t need) {
+  __shared__ uint32_t part[4];
+  const long long id = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  uint32_t total = 0u;
+  if (id < items) {
+    const int w = (int)(id % words);
+    const long long img = id / words;
+    uint32_t keep = 0u;
+    for (int b = 0; b < 32; ++b) {
+      const int co = w * 32 + b;
+      if (co >= c_out) break;
+      uint32_t c = 0u;
+      for (int px = 0; px < hw; ++px) c += (bitmap[(img * hw + px) * words + w] >> b) & 1u;
+      if (mask) {
+        keep |= (c >= need ? 1u : 0u) << b;
+      } else {
+        counts[2 + img * c_out + co] = c;
+        total += c;
+      }
+    }
+    if (mask) mask[img * words + w] = keep;
+  }
+  if (mask) return;
+#pragma unroll
+  for (int sft = 32; sft >= 1; sft >>= 1) total += (uint32_t)__shfl_xor((int)total, sft, 64);
+  if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = total;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    const unsigned long long v = (unsigned long long)part[0] + part[1] + part[2] + part[3];
+    if (v) atomicAdd((unsigned long long*)counts, v);
+  }
+}
+
 template <typename Tr, int NF, int CPS, int PKB, int NWV, int NC, int LDW>
 hipError_t launch_rows_one(const Mfma3Plan& g, const Params& p, const void* w0, const void* w1, hipStream_t s) {
   const long long rows = (long long)p.n * p.ho;
@@ -1166,9 +1204,18 @@ hipError_t launch_mfma3(const Mfma3Plan& g, const Params& p, const void* w0, con
   return launch_rows_dtype<I8Rows>(g, p, w0, w1, s);
 }
 
+namespace {
+constexpr int kSmallMap = 16;   // pixels per feature map up to which the per-thread counting kernel is used
+}
+
 hipError_t launch_bitmap_counts(const Params& p, const uint32_t* bitmap, hipStream_t s) {
   const long long blocks = (long long)p.n * p.words;
   if (blocks <= 0) return hipSuccess;
+  if (p.ho * p.wo <= kSmallMap) {
+    hipLaunchKernelGGL(bitmap_counts_small_kernel, dim3((unsigned)((blocks + 255) / 256)), dim3(256), 0, s, bitmap,
+                       p.words, p.ho * p.wo, p.c_out, blocks, p.counts, (uint32_t*)nullptr, 0u);
+    return hipGetLastError();
+  }
   hipLaunchKernelGGL(bitmap_counts_kernel, dim3((unsigned)blocks), dim3(256), 0, s, bitmap, p.words, p.ho * p.wo,
                      p.c_out, p.counts, (uint32_t*)nullptr, 0u);
   return hipGetLastError();
@@ -1178,6 +1225,11 @@ hipError_t launch_bitmap_chan_mask(const Params& p, const uint32_t* bitmap, uint
                                    hipStream_t s) {
   const long long blocks = (long long)p.n * p.words;
   if (blocks <= 0) return hipSuccess;
+  if (p.ho * p.wo <= kSmallMap) {
+    hipLaunchKernelGGL(bitmap_counts_small_kernel, dim3((unsigned)((blocks + 255) / 256)), dim3(256), 0, s, bitmap,
+                       p.words, p.ho * p.wo, p.c_out, blocks, (uint32_t*)nullptr, mask, need);
+    return hipGetLastError();
+  }
   hipLaunchKernelGGL(bitmap_counts_kernel, dim3((unsigned)blocks), dim3(256), 0, s, bitmap, p.words, p.ho * p.wo,
                      p.c_out, (uint32_t*)nullptr, mask, need);
   return hipGetLastError();

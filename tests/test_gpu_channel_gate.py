@@ -97,3 +97,25 @@ def test_channel_gate_counts_without_bitmap_and_repeat():
         assert np.array_equal(cnt.cpu().numpy().view(np.uint32), ref["counts"])
         assert np.array_equal(y.cpu().numpy(), ref["y"])
     layer.close()
+
+
+SMALL_MAPS = [
+    W.LayerShape("cg_cifar_512@4", 11, 4, 4, 512, 512),                      # 16 pixels per feature map
+    W.LayerShape("cg_fc_256>512_n70", 70, 1, 1, 256, 512, pad=0, k=1),       # one pixel per map: a fully connected layer
+    W.LayerShape("cg_pw_128>96@3", 9, 3, 3, 128, 96 + 32, pad=0, k=1),
+]
+
+
+@pytest.mark.parametrize("shape", SMALL_MAPS, ids=[s.name for s in SMALL_MAPS])
+def test_counts_and_channel_gate_on_maps_of_a_few_pixels(shape):
+    """Fired counts and the channel-wise gate where a feature map has at most 16 pixels (the counting
+    kernel then walks a map per thread)."""
+    q = W.quantize_int8(W.make_inputs(shape, 7300 + shape.c_out, kind="iid", rho=0.35))
+    thr = W.calibrate_gate_int8(q, 0.35, sample_images=None)
+    for tau in (0.0, 0.3, 0.6, 1.0):
+        rep = _say(P.run_int8(q, thr, tau_c=tau, name="%s int8 tau_c=%.2f" % (shape.name, tau)))
+        assert rep.variant in (B.CG_VARIANT_MFMA_ROWS, B.CG_VARIANT_TILE)
+    inp = W.make_inputs(shape, 7400 + shape.c_out, kind="iid", rho=0.3, round_bf16=True)
+    gate = W.calibrate_gate(inp, 0.30, sample_images=None)
+    for tau in (0.0, 0.5):
+        _say(P.run_float(inp, gate, tau_c=tau, name="%s bf16 tau_c=%.2f" % (shape.name, tau)))
