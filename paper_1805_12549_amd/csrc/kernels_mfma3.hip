@@ -962,6 +962,7 @@ hipError_t launch_rows_one(const Mfma3Plan& g, const Params& p, const void* w0, 
   const long long blocks = g.xcd_cb ? tiles * g.n_cb : ((tiles + 7) / 8) * 8 * g.n_cb;
   if (blocks <= 0) return hipSuccess;
   if (blocks > 0x7fffffffll) return hipErrorInvalidValue;
+  if ((long long)g.ni > PKB) return hipErrorInvalidValue;     // the patch must fit its buffer (1 KB per load instruction)
   auto kern = gated_conv_rows_kernel<Tr, NF, CPS, PKB, NWV, NC, LDW>;
   hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(NWV * 64), 0, s, p, g, (const char*)w0, (const char*)w1);
   return hipGetLastError();
@@ -1130,6 +1131,8 @@ Mfma3Plan plan_with(const cg_conv_desc& d, int max_cps, int n_cu) {
         // (with more than two rounds the workgroups no longer run in step and the larger tile wins)
         if ((((rows + tmax - 1) / tmax) * g.n_cb + slots - 1) / slots <= 2)
         for (int tt = tmax; 4 * tt >= 3 * tr && tt >= 1; --tt) {     // (three quarters of the pixel slots stay in use)
+          // (a shorter tile may straddle images where the longer one does not, and then needs more patch rows)
+          if ((long long)patch_rows(tt) * P * sb > c.pkb * 1024) continue;
           const long long wg = ((rows + tt - 1) / tt) * g.n_cb;
           const long long rounds = (wg + slots - 1) / slots;
           const double cost = (double)rounds * (tt + 0.35 * tmax);
