@@ -155,3 +155,69 @@ def test_dense_ops_reject_bad_arguments_before_any_launch():
     with pytest.raises(B.CGError) as e:
         B.cg_avgpool_fc(0, 16, 0, 16, 1, 4, 8, 2)
     assert e.value.code == B.CG_EINVAL
+
+
+def _check(got, ref):
+    tol = P.ATOL + P.RTOL * np.abs(ref) + P.bf16_ulp(ref)
+    err = np.abs(got - ref)
+    assert (err <= tol).all(), "max err %.4g at %s" % (float(err.max()), np.unravel_index(int(err.argmax()), err.shape))
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_dense_ops_on_random_shapes(seed):
+    """Seeded random shapes inside each entry point's documented limits: odd image sizes, every kernel
+    size and stride the input layer takes, channel counts away from the powers of two."""
+    rng = np.random.default_rng(4100 + seed)
+    # input-layer convolution
+    n, h, w = int(rng.integers(1, 4)), int(rng.integers(7, 50)), int(rng.integers(7, 50))
+    c_in, c_out = int(rng.integers(1, 5)), 64 * int(rng.integers(1, 4))
+    k = int(rng.choice([1, 3, 5, 7]))
+    stride, pad = int(rng.integers(1, 3)), int(rng.integers(0, k))
+    x = _bf16(rng.standard_normal((n, h, w, c_in)))
+    wt = _bf16(rng.standard_normal((c_out, k, k, c_in)) * np.sqrt(2.0 / (k * k * c_in)))
+    sc = rng.uniform(0.5, 1.5, c_out).astype(np.float32)
+    sh = (rng.standard_normal(c_out) * 0.1).astype(np.float32)
+    ho, wo = O.out_hw(h, w, k, k, stride, pad)
+    y = torch.empty((n, ho, wo, c_out), dtype=torch.bfloat16, device="cuda")
+    scd, shd = _dev(sc, torch.float32), _dev(sh, torch.float32)
+    print("\n  small_cin_conv n=%d %dx%d c_in=%d c_out=%d k=%d s=%d p=%d" % (n, h, w, c_in, c_out, k, stride, pad), flush=True)
+    xd, wd_ = _dev(x), _dev(wt)           # (held until the kernel has run)
+    B.cg_small_cin_conv(xd.data_ptr(), wd_.data_ptr(), scd.data_ptr(), shd.data_ptr(), y.data_ptr(), n, h, w,
+                        c_in, c_out, k, stride, pad, True, _stream())
+    torch.cuda.synchronize()
+    _check(y.float().cpu().numpy().astype(np.float64), O.dense_conv(x, wt, stride=stride, pad=pad, scale=sc, shift=sh, relu=True))
+    # max pooling
+    n, h, w, c = int(rng.integers(1, 4)), int(rng.integers(1, 40)), int(rng.integers(1, 40)), 8 * int(rng.integers(1, 20))
+    x = _bf16(rng.standard_normal((n, h, w, c)))
+    y = torch.empty((n, (h - 1) // 2 + 1, (w - 1) // 2 + 1, c), dtype=torch.bfloat16, device="cuda")
+    print("  maxpool n=%d %dx%d c=%d" % (n, h, w, c), flush=True)
+    xd = _dev(x)
+    B.cg_maxpool3x3s2(xd.data_ptr(), y.data_ptr(), n, h, w, c, _stream())
+    torch.cuda.synchronize()
+    assert np.array_equal(y.float().cpu().numpy().astype(np.float64), O.maxpool3x3s2(x))
+    # 1x1 convolution with stride
+    n, h, w = int(rng.integers(1, 4)), int(rng.integers(1, 30)), int(rng.integers(1, 30))
+    c_in, c_out, stride = 16 * int(rng.integers(1, 33)), 64 * int(rng.integers(1, 6)), int(rng.integers(1, 4))
+    x = _bf16(rng.standard_normal((n, h, w, c_in)))
+    wt = _bf16(rng.standard_normal((c_out, 1, 1, c_in)) * np.sqrt(2.0 / c_in))
+    sc = rng.uniform(0.5, 1.5, c_out).astype(np.float32)
+    sh = (rng.standard_normal(c_out) * 0.1).astype(np.float32)
+    y = torch.empty((n, (h - 1) // stride + 1, (w - 1) // stride + 1, c_out), dtype=torch.bfloat16, device="cuda")
+    scd, shd = _dev(sc, torch.float32), _dev(sh, torch.float32)
+    print("  pointwise n=%d %dx%d c_in=%d c_out=%d s=%d" % (n, h, w, c_in, c_out, stride), flush=True)
+    xd, wd_ = _dev(x), _dev(wt.reshape(c_out, c_in))
+    B.cg_pointwise_conv(xd.data_ptr(), wd_.data_ptr(), scd.data_ptr(), shd.data_ptr(),
+                        y.data_ptr(), n, h, w, c_in, c_out, stride, False, _stream())
+    torch.cuda.synchronize()
+    _check(y.float().cpu().numpy().astype(np.float64), O.dense_conv(x, wt, stride=stride, pad=0, scale=sc, shift=sh, relu=False))
+    # average pooling + classifier
+    n, hw, c, classes = int(rng.integers(1, 6)), int(rng.integers(1, 60)), 8 * int(rng.integers(1, 200)), int(rng.integers(1, 1100))
+    x = _bf16(np.maximum(rng.standard_normal((n, hw, c)), 0))
+    wfc = _bf16(rng.standard_normal((classes, c)) / np.sqrt(c))
+    b = rng.standard_normal(classes).astype(np.float32)
+    out = torch.empty((n, classes), dtype=torch.float32, device="cuda")
+    print("  avgpool_fc n=%d hw=%d c=%d classes=%d" % (n, hw, c, classes), flush=True)
+    xd, wd_, bd = _dev(x), _dev(wfc), _dev(b, torch.float32)
+    B.cg_avgpool_fc(xd.data_ptr(), wd_.data_ptr(), bd.data_ptr(), out.data_ptr(), n, hw, c, classes, _stream())
+    torch.cuda.synchronize()
+    np.testing.assert_allclose(out.cpu().numpy(), O.avgpool_fc(x, wfc, b), rtol=P.RTOL, atol=P.ATOL)
