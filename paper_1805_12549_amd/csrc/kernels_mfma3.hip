@@ -998,11 +998,11 @@ unsigned magic_of3(int d) { return d == 1 ? 0u : (unsigned)(((1ull << 32) + (uns
 }  // namespace
 
 namespace {
-Mfma3Plan plan_with(const cg_conv_desc& d, int max_cps, int n_cu);
+Mfma3Plan plan_with(const cg_conv_desc& d, int max_cps, int n_cu, bool strict);
 }
 
 Mfma3Plan mfma3_plan(const cg_conv_desc& d, int n_cu) {
-  Mfma3Plan g = plan_with(d, 4, n_cu);
+  Mfma3Plan g = plan_with(d, 4, n_cu, true);
   if (g.ok && g.cps == 4 && g.pkb == 48) {
     // Four-chunk super-stages need the 48 KB patch buffers here (one workgroup per CU).  If the grid has
     // more workgroups than CUs and two-chunk super-stages fit the 24 KB class, two workgroups per CU
@@ -1010,15 +1010,21 @@ Mfma3Plan mfma3_plan(const cg_conv_desc& d, int n_cu) {
     const int ho = (d.h + 2 * d.pad - 3) / d.stride + 1;
     const long long wg = (((long long)d.n_max * ho + g.tr - 1) / g.tr) * g.n_cb;
     if (wg > n_cu) {
-      const Mfma3Plan h = plan_with(d, 2, n_cu);
+      const Mfma3Plan h = plan_with(d, 2, n_cu, true);
       if (h.ok && h.pkb == 24) return h;
     }
   }
+  // Wide images with a large patch per output row (stride 2, many channels per super-stage): two-chunk
+  // super-stages halve the patch; failing that, a tile that fills less than three quarters of its
+  // pixel slots still beats the plain kernel by far.
+  if (!g.ok) g = plan_with(d, 2, n_cu, true);
+  if (!g.ok) g = plan_with(d, 4, n_cu, false);
+  if (!g.ok) g = plan_with(d, 2, n_cu, false);
   return g;
 }
 
 namespace {
-Mfma3Plan plan_with(const cg_conv_desc& d, int max_cps, int n_cu) {
+Mfma3Plan plan_with(const cg_conv_desc& d, int max_cps, int n_cu, bool strict) {
   Mfma3Plan g{};
   g.ok = 0;
   if (d.in_dtype != CG_BF16 && d.in_dtype != CG_I8) return g;
@@ -1117,7 +1123,7 @@ Mfma3Plan plan_with(const cg_conv_desc& d, int max_cps, int n_cu) {
       if (tr > rows) tr = (int)rows;
       int t = tr;
       while (t >= 1 && (long long)patch_rows(t) * P * sb > c.pkb * 1024) --t;
-      if (t < 1 || 4 * t < 3 * tr) continue;
+      if (t < 1 || (strict && 4 * t < 3 * tr)) continue;
       if (nf == 2 && ((rows + t - 1) / t) * g.n_cb < n_cu) continue;   // the large tile only when it still fills the CUs
       {
         // Balance the grid: with fewer rows per tile the tiles may come out as a whole number of

@@ -52,6 +52,9 @@ RANDOM = _shapes(int(_ENV[0]), int(_ENV[1]), large=len(_ENV) > 2)
 # shapes that once failed: a tile height chosen for balance made the tiles straddle images, and the
 # straddling tiles' patch no longer fitted its LDS buffer
 RANDOM += [W.LayerShape("fixed_6x32x31_384>128_k3s1p1g4", 6, 32, 31, 384, 128, stride=1, pad=1, k=3, groups=4)]
+# a wide stride-2 image with many channels: its patch fits only with two-chunk super-stages or a
+# part-filled tile (once left to the plain kernel)
+RANDOM += [W.LayerShape("fixed_1x37x64_384>512_k3s2p1g4", 1, 37, 64, 384, 512, stride=2, pad=1, k=3, groups=4)]
 
 
 @pytest.mark.parametrize("shape", RANDOM, ids=[s.name for s in RANDOM])
@@ -95,5 +98,11 @@ def test_random_shape_bf16_and_int8(shape):
     if shape.c_base % 16 == 0:
         q = W.quantize_int8(W.make_inputs(shape, 9100 + len(shape.name) + shape.h * 31 + shape.w, kind=kind, rho=rho))
         thr = W.calibrate_gate_int8(q, rho, sample_images=None)
+        rq = W.requant_params(q, rng)
+        res8 = rng.integers(-128, 128, (shape.n, shape.ho, shape.wo, c)).astype(np.int8)
         for v in variants:
-            _say(P.run_int8(q, thr, variant=v, n_run=n_run, name="%s int8 variant %d" % (shape.name, v)))
+            if rng.random() < 0.5:
+                _say(P.run_int8(q, thr, variant=v, n_run=n_run, name="%s int8 variant %d" % (shape.name, v)))
+            else:
+                _say(P.run_int8(q, thr, out_i8=True, rq=rq, residual=res8, rq_res_mult=1 << 14, variant=v, n_run=n_run,
+                                epilogue=B.CG_EPI_RESIDUAL | B.CG_EPI_RELU, name="%s int8 requantised variant %d" % (shape.name, v)))
