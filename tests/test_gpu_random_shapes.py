@@ -87,6 +87,17 @@ def test_random_shape_bf16_and_int8(shape):
             variants.append(B.CG_VARIANT_TILE)
         except B.CGError as e:
             assert e.code == B.CG_EUNSUPPORTED       # (wide images whose patch rows do not fit its stage buffers)
+    # the large-tile kernel with a forced tile shape (wavefront fragments, channel split, stage width)
+    hint = int(rng.choice([1, 2, 4])) | (int(rng.choice([1, 2])) << 4) | (int(rng.choice([0, 0, 1, 2, 4, 8])) << 8)
+    try:
+        _say(P.run_float(inp, gate, out_dtype=B.CG_BF16, variant=B.CG_VARIANT_TILE, tile_hint=hint, n_run=n_run,
+                         name="%s bf16 tile hint %#x" % (shape.name, hint)))
+        if shape.c_base % 16 == 0:
+            q8 = W.quantize_int8(W.make_inputs(shape, 9300 + shape.h * 31 + shape.w, kind=kind, rho=rho))
+            _say(P.run_int8(q8, W.calibrate_gate_int8(q8, rho, sample_images=None), variant=B.CG_VARIANT_TILE, tile_hint=hint,
+                            n_run=n_run, name="%s int8 tile hint %#x" % (shape.name, hint)))
+    except B.CGError as e:
+        assert e.code == B.CG_EUNSUPPORTED           # a tile shape this layer cannot take
     if shape.c_out % shape.groups == 0 and rng.random() < 0.4:
         # the same shape with channel grouping (output group i takes input group i as its base), shuffled store
         ginp = W.make_inputs(shape, 9200 + shape.h * 31 + shape.w, kind=kind, rho=rho, round_bf16=True, grouped=True)
