@@ -128,6 +128,10 @@ struct Mfma3Plan {
   // conditional phase all c_in channels, the packed weights holding zeros where a channel is not on
   // that path for that output channel.
   int grp_mode, gsp;
+  // set by the launcher for the call's grid: ceil(tiles / 8); the divisor that splits a block slot into
+  // (tile, channel block) and its multiplier (0: divide)
+  int tiles8, div_d;
+  unsigned div_magic;
   int stages[2];           // super-stages of the base / conditional phase
   size_t wpk_base_bytes, wpk_cond_bytes;
 };

@@ -262,15 +262,20 @@ __global__ __launch_bounds__(NWV * 64, 2) void gated_conv_rows_kernel(
   int tile, cbk;
   {
     const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+    // slot / div_d without a division sequence (the launcher picks the multiplier where it is exact)
+    int q;
+    if (g.div_magic)
+      q = (int)__umulhi((unsigned)slot, g.div_magic);
+    else if (g.div_d == 1)
+      q = slot;
+    else
+      q = slot / g.div_d;
     if (g.xcd_cb) {
-      const int ncb8 = g.n_cb >> 3;
-      tile = slot / ncb8;
-      cbk = (slot - tile * ncb8) * 8 + xcd;
+      tile = q;                                     // div_d = n_cb / 8
+      cbk = (slot - q * g.div_d) * 8 + xcd;
     } else {
-      const int grp = slot / g.n_cb;
-      cbk = slot - grp * g.n_cb;
-      const int tiles = (p.n * p.ho + g.tr - 1) / g.tr;
-      tile = xcd * ((tiles + 7) >> 3) + grp;        // an XCD takes a contiguous run of tiles: neighbours share halo rows in its L2
+      cbk = slot - q * g.div_d;                     // div_d = n_cb
+      tile = xcd * g.tiles8 + q;                    // an XCD takes a contiguous run of tiles: neighbours share halo rows in its L2
     }
   }
   const int total_rows = p.n * p.ho;
@@ -281,18 +286,6 @@ __global__ __launch_bounds__(NWV * 64, 2) void gated_conv_rows_kernel(
   const int S = S0 + ((p.gated && !p.gate_only) ? g.stages[1] : 0);   // a gate-only pass stops after the base phase
   const int G = 3 * S;                              // weight granules
   const int eb = g.elem_bytes;
-
-  // gate thresholds of this channel block: the loads go out first, the LDS copy follows later
-  acc_t my_lo = 0, my_hi = 0;
-  if (tid < 64) {
-    const int co = cbk * kBn + tid;
-    if constexpr (Base::kDtype == CG_I8) {
-      my_lo = p.thr_i[co];
-    } else {
-      my_lo = p.thr_f[co];
-      my_hi = p.thr_hi_f[co];
-    }
-  }
 
   // weight granule j (3*super-stage + kernel row, counted over both phases) of this channel block
   // sits at wbase0 + j*GB in the base phase and at wcond0 + (j - 3*S0)*GB in the conditional phase
@@ -382,6 +375,20 @@ __global__ __launch_bounds__(NWV * 64, 2) void gated_conv_rows_kernel(
       if (((smask >> k) & 1u) && voff[k] >= 0) lds_direct16(xs0 + voff[k], pat2 + (lw + NLW * k) * 1024);
   }
 
+  // Gate thresholds of this channel block.  The loads go out after the first LDS-direct loads (an
+  // ordinary load that the compiler waits for early would make it wait for those as well, before the
+  // patch loads are even issued); the copy to LDS is the last thing before the first barrier.
+  acc_t my_lo = 0, my_hi = 0;
+  if (tid < 64) {
+    const int co = cbk * kBn + tid;
+    if constexpr (Base::kDtype == CG_I8) {
+      my_lo = p.thr_i[co];
+    } else {
+      my_lo = p.thr_f[co];
+      my_hi = p.thr_hi_f[co];
+    }
+  }
+
   // ---- this lane's base-path pixels ------------------------------------------------------------
   int pix[NF];
   int pimg[NF];         // image of the pixel
@@ -403,17 +410,6 @@ __global__ __launch_bounds__(NWV * 64, 2) void gated_conv_rows_kernel(
     for (int c = 0; c < 3; ++c) pa[fp][c] = slot_addr<CPS>(slot + c, lh);
   }
   for (int i = tid; i < 2 * BM; i += NT) bmp[i] = 0u;
-  if (tid < 64) {
-    tlo[tid] = my_lo;
-    thi[tid] = my_hi;
-    if (Base::kDtype != CG_I8 && (p.epilogue & CG_EPI_AFFINE)) {
-      const int co = cbk * kBn + tid;
-      aff[tid] = p.sc0[co];
-      aff[64 + tid] = p.sh0[co];
-      aff[128 + tid] = p.sc1[co];
-      aff[192 + tid] = p.sh1[co];
-    }
-  }
 
   acc16 accP[NF][NC], accR[NF][NC];
 #pragma unroll
@@ -438,6 +434,17 @@ __global__ __launch_bounds__(NWV * 64, 2) void gated_conv_rows_kernel(
   int n_act = 0;        // fired pixels of the tile
   const int wofs = lh * 1024 + lj * 16 + fc0 * 512;   // lane's offset of its weight rows in a granule
 
+  if (tid < 64) {
+    tlo[tid] = my_lo;
+    thi[tid] = my_hi;
+    if (Base::kDtype != CG_I8 && (p.epilogue & CG_EPI_AFFINE)) {
+      const int co = cbk * kBn + tid;
+      aff[tid] = p.sc0[co];
+      aff[64 + tid] = p.sh0[co];
+      aff[128 + tid] = p.sc1[co];
+      aff[192 + tid] = p.sh1[co];
+    }
+  }
   __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): the first granules and the first patch have landed
   __syncthreads();
 
@@ -963,8 +970,14 @@ hipError_t launch_rows_one(const Mfma3Plan& g, const Params& p, const void* w0, 
   if (blocks <= 0) return hipSuccess;
   if (blocks > 0x7fffffffll) return hipErrorInvalidValue;
   if ((long long)g.ni > PKB) return hipErrorInvalidValue;     // the patch must fit its buffer (1 KB per load instruction)
+  Mfma3Plan gg = g;
+  gg.tiles8 = (int)((tiles + 7) / 8);
+  gg.div_d = g.xcd_cb ? g.n_cb >> 3 : g.n_cb;
+  gg.div_magic = 0u;
+  if (gg.div_d > 1 && (blocks >> 3) * gg.div_d < (1ll << 32))   // exact for every slot of this grid
+    gg.div_magic = (unsigned)(((1ull << 32) + (unsigned)gg.div_d - 1) / (unsigned)gg.div_d);
   auto kern = gated_conv_rows_kernel<Tr, NF, CPS, PKB, NWV, NC, LDW>;
-  hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(NWV * 64), 0, s, p, g, (const char*)w0, (const char*)w1);
+  hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(NWV * 64), 0, s, p, gg, (const char*)w0, (const char*)w1);
   return hipGetLastError();
 }
 
